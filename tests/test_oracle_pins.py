@@ -1,0 +1,271 @@
+"""Pins for the fp64 oracle: closed forms, invariants, special cases, brute force.
+
+None of these re-types the oracle's formula: each checks it against something the
+mathematics fixes independently, chosen so that a dropped term, a wrong sign or
+index, or a transposed operand fails at least one of them.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import scipy.special
+
+from oracle import oracle, tiny_loops
+
+RNG = lambda seed: np.random.Generator(np.random.PCG64(seed))
+
+
+def _rand_problem(seed, B, D, C, scale=1.0, bias=True):
+    r = RNG(seed)
+    X = r.standard_normal((B, D)) * scale
+    W = r.standard_normal((C, D)) * scale
+    b = r.standard_normal(C) if bias else None
+    y = r.integers(0, C, size=B)
+    return X, W, b, y
+
+
+# P1 -- uniform logits: lse = b + ln C, loss = ln C, dZ = 1/C - onehot.
+@pytest.mark.parametrize("C", [2, 1000, 100_000])
+def test_uniform_logits_closed_form(C):
+    B, D = 5, 3
+    X = RNG(1).standard_normal((B, D))
+    W = np.zeros((C, D))
+    b = np.full(C, 0.75)
+    y = np.array([0, C - 1, C // 2, 1 % C, 0])
+    out = oracle.unsharded(X, W, b, y)
+    assert np.allclose(out["lse"], 0.75 + math.log(C), rtol=0, atol=1e-12)
+    assert np.allclose(out["loss"], math.log(C), rtol=0, atol=1e-12)
+    expect = np.full((B, C), 1.0 / C)
+    expect[np.arange(B), y] -= 1.0
+    assert np.allclose(out["dZ"], expect, rtol=0, atol=1e-15)
+    assert np.allclose(out["dX"], 0.0, atol=1e-15)      # W = 0
+    # dW[c, :] = sum_i dZ[i, c] X[i, :]
+    cnt = np.zeros((C, D))
+    np.add.at(cnt, y, X)
+    assert np.allclose(out["dW"], X.sum(0)[None, :] / C - cnt, atol=1e-12)
+
+
+def test_ln_values_printed():
+    # the two constants the uniform case must hit for the workloads' class counts
+    out = oracle.unsharded(np.ones((1, 1)), np.zeros((1000, 1)), None, np.array([3]))
+    assert abs(out["loss"][0] - 6.907755278982137) < 1e-12
+    out = oracle.unsharded(np.ones((1, 1)), np.zeros((100_000, 1)), None, np.array([3]))
+    assert abs(out["loss"][0] - 11.512925464970229) < 1e-12
+
+
+# P2 -- hand-worked example: x = 1, w = (0, ln 2, ln 3), y = 2.
+def test_hand_example_three_classes():
+    X = np.array([[1.0]])
+    W = np.array([[0.0], [math.log(2.0)], [math.log(3.0)]])
+    out = oracle.unsharded(X, W, None, np.array([2]))
+    assert abs(out["lse"][0] - math.log(6.0)) < 1e-14
+    assert abs(out["loss"][0] - math.log(2.0)) < 1e-14
+    assert np.allclose(out["dZ"][0], [1 / 6, 1 / 3, -1 / 2], atol=1e-15)
+    assert abs(out["dX"][0, 0] - (math.log(2.0) / 3 - math.log(3.0) / 2)) < 1e-14
+    assert np.allclose(out["dW"][:, 0], [1 / 6, 1 / 3, -1 / 2], atol=1e-15)   # x = 1
+    assert np.allclose(out["db"], [1 / 6, 1 / 3, -1 / 2], atol=1e-15)
+    # an asymmetric version (x = 2, D = 2) that separates dW's two axes
+    X = np.array([[2.0, -1.0]])
+    W = np.array([[0.0, 0.0], [math.log(2.0) / 2, 0.0], [0.0, -math.log(3.0)]])
+    out = oracle.unsharded(X, W, None, np.array([0]))
+    p = np.array([1 / 6, 1 / 3, 1 / 2])
+    dz = p - np.array([1.0, 0, 0])
+    assert np.allclose(out["dW"], np.outer(dz, X[0]), atol=1e-15)
+    assert np.allclose(out["dX"][0], dz @ W, atol=1e-15)
+
+
+# P3 -- two classes reduce to logistic regression.
+def test_two_class_is_logistic():
+    X, W, b, y = _rand_problem(3, 17, 4, 2)
+    out = oracle.unsharded(X, W, b, y)
+    for i in range(17):
+        z = [float(X[i] @ W[c] + b[c]) for c in range(2)]
+        d = z[1 - y[i]] - z[y[i]]
+        softplus = max(d, 0.0) + math.log1p(math.exp(-abs(d)))
+        assert abs(out["loss"][i] - softplus) < 1e-12
+        sig = 1.0 / (1.0 + math.exp(-d))          # probability of the wrong class
+        assert abs(out["dZ"][i, 1 - y[i]] - sig) < 1e-12
+        assert abs(out["dZ"][i, y[i]] + sig) < 1e-12
+
+
+# P4 -- invariants.
+def test_gradient_invariants():
+    X, W, b, y = _rand_problem(4, 9, 6, 11)
+    out = oracle.unsharded(X, W, b, y)
+    assert np.allclose(out["dZ"].sum(axis=1), 0.0, atol=1e-14)
+    assert abs(out["db"].sum()) < 1e-13
+    assert np.allclose(out["dW"].sum(axis=0), 0.0, atol=1e-13)
+    # adding a constant to every bias changes nothing
+    out2 = oracle.unsharded(X, W, b + 3.25, y)
+    assert np.allclose(out2["loss"], out["loss"], atol=1e-12)
+    assert np.allclose(out2["dW"], out["dW"], atol=1e-12)
+    assert np.allclose(out2["lse"], out["lse"] + 3.25, atol=1e-12)
+    # all class rows equal -> dX = 0
+    Weq = np.tile(W[:1], (11, 1))
+    assert np.allclose(oracle.unsharded(X, Weq, b, y)["dX"], 0.0, atol=1e-13)
+    # linear in g
+    out3 = oracle.unsharded(X, W, b, y, g=0.125)
+    for k in ("dZ", "dX", "dW", "db"):
+        assert np.allclose(out3[k], 0.125 * out[k], rtol=1e-14, atol=0)
+    assert np.allclose(out3["loss"], out["loss"])
+    assert abs(out["loss_mean"] - sum(out["loss"]) / 9) < 1e-14
+
+
+# P5 -- partition invariance (Section 2.1: the concatenation of the slice matmuls is the product).
+@pytest.mark.parametrize("widths", [[13], [7, 6], [1, 1, 11], [1] * 13, [5, 3, 4, 1], [12, 1]])
+def test_partition_invariance(widths):
+    B, D, C = 10, 5, 13
+    X, W, b, y = _rand_problem(5, B, D, C, scale=2.0)
+    full = oracle.unsharded(X, W, b, y, g=0.5)
+    ms, ss, ts, offs = [], [], [], []
+    o = 0
+    hits = np.zeros(B, dtype=int)
+    for w in widths:
+        m, s, t = oracle.partials(X, W[o:o + w], b[o:o + w], y, o)
+        inside, local = oracle.membership(y, o, w)
+        hits += inside
+        assert np.array_equal(local[inside], y[inside] - o)
+        assert np.all(t[~inside] == 0.0)
+        ms.append(m), ss.append(s), ts.append(t), offs.append(o)
+        o += w
+    assert np.array_equal(hits, np.ones(B, dtype=int))          # exactly one shard owns each label
+    lse, loss = oracle.combine(ms, ss, ts)
+    assert np.allclose(lse, full["lse"], rtol=1e-12, atol=0)
+    assert np.allclose(loss, full["loss"], rtol=1e-12, atol=1e-13)
+    # row max over shards is the unsharded max and the label logit the unsharded one
+    # (to BLAS rounding: a slice matmul may sum in another order than the full one)
+    Z = oracle.logits(X, W, b)
+    assert np.allclose(np.max(np.stack(ms), axis=0), Z.max(axis=1), rtol=1e-13, atol=1e-14)
+    assert np.allclose(np.sum(np.stack(ts), axis=0), Z[np.arange(B), y], rtol=1e-13, atol=1e-14)
+    dX = np.zeros((B, D))
+    for o, w in zip(offs, widths):
+        g = oracle.shard_grads(X, W[o:o + w], b[o:o + w], lse, y, o, g=0.5)
+        assert np.allclose(g["dW"], full["dW"][o:o + w], rtol=1e-11, atol=1e-13)
+        assert np.allclose(g["db"], full["db"][o:o + w], rtol=1e-11, atol=1e-13)
+        assert np.allclose(g["dZ"], full["dZ"][:, o:o + w], rtol=1e-11, atol=1e-14)
+        dX += g["dX_partial"]
+    assert np.allclose(dX, full["dX"], rtol=1e-11, atol=1e-13)
+
+
+# P6 -- central finite differences of the summed loss.
+def test_finite_differences():
+    B, D, C = 3, 4, 5
+    X, W, b, y = _rand_problem(6, B, D, C)
+    out = oracle.unsharded(X, W, b, y)
+    h = 1e-6
+
+    def total(Xv, Wv, bv):
+        return float(oracle.unsharded(Xv, Wv, bv, y)["loss"].sum())
+
+    for arr, key in ((X, "dX"), (W, "dW"), (b, "db")):
+        num = np.zeros_like(arr)
+        it = np.nditer(arr, flags=["multi_index"])
+        for _ in it:
+            idx = it.multi_index
+            save = arr[idx]
+            arr[idx] = save + h
+            fp = total(X, W, b)
+            arr[idx] = save - h
+            fm = total(X, W, b)
+            arr[idx] = save
+            num[idx] = (fp - fm) / (2 * h)
+        assert np.allclose(num, out[key], rtol=1e-6, atol=1e-8), key
+
+
+# P7 -- a library routine for the log-sum-exp special case.
+def test_against_scipy_logsumexp():
+    X, W, b, y = _rand_problem(7, 12, 8, 40, scale=3.0)
+    Z = X @ W.T + b
+    out = oracle.unsharded(X, W, b, y)
+    assert np.allclose(out["lse"], scipy.special.logsumexp(Z, axis=1), rtol=1e-13)
+    assert np.allclose(out["dZ"] + np.eye(40)[y], scipy.special.softmax(Z, axis=1), rtol=1e-11, atol=1e-15)
+
+
+# P8 -- pure-Python loops on tiny inputs.
+@pytest.mark.parametrize("seed,B,D,C", [(8, 4, 3, 6), (9, 8, 8, 16), (10, 1, 1, 1)])
+def test_brute_force_loops(seed, B, D, C):
+    X, W, b, y = _rand_problem(seed, B, D, C)
+    out = oracle.unsharded(X, W, b, y, g=1.5)
+    lse, loss, dX, dW, db = tiny_loops.forward_backward(X.tolist(), W.tolist(), b.tolist(), y.tolist(), g=1.5)
+    assert np.allclose(out["lse"], lse, rtol=1e-13)
+    assert np.allclose(out["loss"], loss, rtol=1e-12, atol=1e-13)
+    assert np.allclose(out["dX"], dX, rtol=1e-12, atol=1e-13)
+    assert np.allclose(out["dW"], dW, rtol=1e-12, atol=1e-13)
+    assert np.allclose(out["db"], db, rtol=1e-12, atol=1e-13)
+    if C >= 3:
+        lo, hi = 1, C - 1
+        m, s, t = oracle.partials(X, W[lo:hi], b[lo:hi], y, lo)
+        m2, s2, t2 = tiny_loops.shard_partials(X.tolist(), W.tolist(), b.tolist(), y.tolist(), lo, hi)
+        assert np.allclose(m, m2, rtol=1e-13) and np.allclose(s, s2, rtol=1e-13)
+        assert np.allclose(t, t2, rtol=1e-13, atol=0)
+
+
+# P9 -- the integer part: membership and local index, read through the outputs.
+def test_membership_through_outputs():
+    B, D, C = 64, 2, 50
+    r = RNG(11)
+    y = r.integers(0, C, size=B)
+    X = r.standard_normal((B, D))
+    W = np.zeros((C, D))
+    b = np.arange(C, dtype=np.float64)
+    owners = np.zeros(B, dtype=int)
+    for o, w in [(0, 7), (7, 1), (8, 30), (38, 12)]:
+        m, s, t = oracle.partials(X, W[o:o + w], b[o:o + w], y, o)
+        inside = (y >= o) & (y < o + w)
+        assert np.array_equal(t, np.where(inside, y.astype(np.float64), 0.0))
+        owners += inside
+        # W = 0, b = 0: db recovers the label histogram
+        g = oracle.shard_grads(X, W[o:o + w], None, np.full(B, math.log(C)), y, o)
+        hist = np.bincount(y[inside] - o, minlength=w)
+        assert np.allclose(g["db"], B / C - hist, atol=1e-12)
+    assert np.array_equal(owners, np.ones(B, dtype=int))
+    # boundary labels
+    ins, loc = oracle.membership(np.array([4, 5, 9, 10]), 5, 5)
+    assert ins.tolist() == [False, True, True, False]
+    assert loc.tolist()[1:3] == [0, 4]
+
+
+# P10 -- asymptotes and overflow safety.
+def test_dominant_logit_and_large_magnitudes():
+    C = 6
+    X = np.array([[1.0]])
+    W = np.zeros((C, 1))
+    W[2, 0] = 800.0                      # exp(800) overflows without the max shift
+    at_label = oracle.unsharded(X, W, None, np.array([2]))
+    assert np.isfinite(at_label["lse"][0]) and abs(at_label["lse"][0] - 800.0) < 1e-12
+    assert abs(at_label["loss"][0]) < 1e-12 and np.allclose(at_label["dZ"], 0.0, atol=1e-12)
+    off_label = oracle.unsharded(X, W, None, np.array([0]))
+    assert abs(off_label["loss"][0] - 800.0) < 1e-9
+    assert np.allclose(off_label["dZ"][0], [-1, 0, 1, 0, 0, 0], atol=1e-12)
+    # very negative logits must not underflow to log(0)
+    out = oracle.unsharded(X, -W - 900.0 * (np.arange(C)[:, None] != 2), None, np.array([1]))
+    assert np.all(np.isfinite(out["lse"])) and np.all(np.isfinite(out["loss"]))
+    # shard-wise statistics stay finite too, and combine to the same thing
+    parts = [oracle.partials(X, W[o:o + 3], None, np.array([0]), o) for o in (0, 3)]
+    lse, loss = oracle.combine(*zip(*parts))
+    assert abs(lse[0] - 800.0) < 1e-12 and abs(loss[0] - 800.0) < 1e-9
+
+
+def test_chunked_equals_unchunked():
+    X, W, b, y = _rand_problem(12, 37, 6, 19)
+    a = oracle.unsharded(X, W, b, y, g=0.3)
+    c = oracle.unsharded_chunked(X, W, b, y, g=0.3, rows_per_chunk=8)
+    for k in ("lse", "loss", "dX", "dW", "db"):
+        assert np.allclose(a[k], c[k], rtol=1e-12, atol=1e-13), k
+
+
+def test_paper_sizes_fixture():
+    """The sizes the paper prints fix D = 2048, C = 100 000, fp32, with a bias."""
+    vals = {}
+    with open(os.path.join(os.path.dirname(__file__), "golden", "paper_sizes.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                k, v = line.split()
+                vals[k] = float(v)
+    C = int(vals["classes"])
+    fc_mib = (2048 * C + C) * 4 / 2**20
+    assert round(fc_mib) == vals["fc_param_mb"]
+    assert round(2048 * C * 4 / 2**20) != vals["fc_param_mb"]         # without the bias it would print 781
+    share = vals["fc_param_mb"] / (vals["fc_param_mb"] + vals["resnet50_param_mb"])
+    assert round(100 * share, 1) == vals["sync_reduction_percent"]
