@@ -1,0 +1,134 @@
+/* libwhalesplit -- the single-GPU hot path of a class-column-split fully-connected
+ * layer with softmax cross-entropy, for AMD MI355X (gfx950).
+ *
+ * Background (Whale, arXiv 2011.09208).  The paper's motivating workload is a
+ * ResNet50 feature extractor feeding a 100 000-class fully-connected layer and a
+ * softmax (Section 1; Section 2.1).  Under its `split` primitive (Section 3.1.2,
+ * the replicate/split listing) the FC weight is cut along the class dimension
+ * (ShardingInfo [0, 1], Section 3.2.2); each device multiplies the features by its
+ * own slice, and the slices' outputs concatenate to the full product (Section 2.1,
+ * "Tensor Model Parallelism").  Shard widths may be uneven (Section 3.3.1).  This
+ * library is what ONE device runs for its shard; several shards can be evaluated
+ * one after another on the same GPU and merged with ws_combine_partials.
+ *
+ * Notation.  B rows (samples), D features, C_shard classes in this shard, which
+ * covers global class ids [class_offset, class_offset + C_shard).
+ *   z[i][c] = sum_d X[i][d] * W[c][d] + b[c]
+ * Inputs are bfloat16, every accumulation is fp32.
+ *
+ * Memory.  EVERY pointer is a DEVICE pointer owned by the caller.  The library
+ * allocates nothing, never synchronises the host, and enqueues all work on
+ * `stream` (a hipStream_t passed as void*; NULL = the default stream).  Inputs are
+ * never modified; outputs are fully overwritten unless stated; buffers must not
+ * overlap.  Workspaces are caller-owned scratch whose contents are unspecified
+ * after the call; size them with the *_workspace_bytes queries.
+ *
+ * Layout.  Matrices are row-major with a row pitch given in ELEMENTS.  W is stored
+ * class-major, [C_shard][D] (the paper's [D, C] matrix transposed), so a column
+ * shard of the layer is a contiguous slab of rows and both GEMM operands of the
+ * logits product are contiguous along the contraction.
+ *
+ * Errors.  Every entry point returns a ws_status.  Arguments are validated on the
+ * host before any HIP call, so the WS_ERR_NULL/SHAPE/ALIGN/RANGE/WORKSPACE paths
+ * need no GPU.  Requirements: B, D, C_shard > 0; D a multiple of 64; pitches >= D
+ * (>= C for the statistics stride) and multiples of 8 elements; matrix base
+ * pointers 16-byte aligned, fp32/int32 vectors 4-byte aligned;
+ * class_offset >= 0 and class_offset + C_shard <= INT32_MAX.  Labels live on the
+ * device and are not range-checked: a label outside the shard simply matches no
+ * class of it.  A HIP launch failure is reported as WS_ERR_HIP.
+ */
+#ifndef WHALESPLIT_H
+#define WHALESPLIT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    WS_OK = 0,
+    WS_ERR_NULL = 1,       /* a required pointer is NULL */
+    WS_ERR_SHAPE = 2,      /* non-positive size, D not a multiple of 64, pitch < row length */
+    WS_ERR_ALIGN = 3,      /* pointer or pitch not aligned as required */
+    WS_ERR_RANGE = 4,      /* class_offset negative or class range overflows int32; S out of range */
+    WS_ERR_WORKSPACE = 5,  /* workspace NULL or smaller than the query says */
+    WS_ERR_HIP = 6         /* the HIP runtime refused a launch */
+} ws_status;
+
+/* Human-readable name of a status code (static storage; never NULL). */
+const char* ws_status_string(int status);
+
+/* Library version, major * 1000 + minor. */
+int ws_version(void);
+
+/* Bytes of scratch ws_split_fc_fwd needs for this shape (0 on invalid shape). */
+size_t ws_fwd_workspace_bytes(int32_t B, int32_t D, int32_t C_shard);
+
+/* Forward call of one shard (Section 2.1 split matmul; Section 3.1.2 FC + Softmax
+ * inside one split scope).  Computes the shard's logits tile by tile on the matrix
+ * cores and reduces them in the GEMM epilogue; the [B, C_shard] logits are never
+ * written to memory.  Per row i:
+ *   row_max[i]     = max_c z[i][c]                       over the shard's classes
+ *   row_sumexp[i]  = sum_c exp(z[i][c] - row_max[i])
+ *   label_logit[i] = z[i][labels[i] - class_offset] if the label lies in the shard,
+ *                    else exactly 0.0f
+ * X        bf16 [B][ldx]        W_shard  bf16 [C_shard][ldw]
+ * b_shard  fp32 [C_shard] or NULL (= zero bias)
+ * labels   int32 [B], GLOBAL class ids
+ * outputs  fp32 [B] each
+ */
+int ws_split_fc_fwd(const void* X, int64_t ldx,
+                    const void* W_shard, int64_t ldw,
+                    const float* b_shard,
+                    const int32_t* labels,
+                    int32_t B, int32_t D, int32_t C_shard, int32_t class_offset,
+                    float* row_max, float* row_sumexp, float* label_logit,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
+/* Merge the statistics of S shards evaluated on this GPU (no collectives):
+ *   m = max_s row_max[s];  sum = sum_s row_sumexp[s] * exp(row_max[s] - m)
+ *   logsumexp = m + log(sum);  loss_rows = logsumexp - sum_s label_logit[s]
+ * The three inputs are [S][shard_stride] fp32 arrays (row i of shard s at
+ * s * shard_stride + i), shard_stride >= B, 1 <= S <= 65536.
+ * loss_mean, if not NULL, receives the mean of loss_rows (one float).
+ * This replaces the all-gather of logits the paper's split matmul would need
+ * (Section 2.1) by an exchange of three floats per row.
+ */
+int ws_combine_partials(const float* row_max, const float* row_sumexp, const float* label_logit,
+                        int32_t S, int32_t B, int64_t shard_stride,
+                        float* logsumexp, float* loss_rows, float* loss_mean,
+                        void* stream);
+
+/* Bytes of scratch ws_split_fc_bwd needs for this shape (0 on invalid shape). */
+size_t ws_bwd_workspace_bytes(int32_t B, int32_t D, int32_t C_shard);
+
+/* Backward call of one shard, given the combined log-sum-exp of all shards.
+ * Recomputes the shard's logits exactly as the forward call does, then
+ *   dz[i][c]   = grad_scale * (exp(z[i][c] - logsumexp[i]) - [labels[i] == class_offset + c])
+ *   dX_partial = dz . W_shard      fp32 [B][lddx]  (overwritten, or += if accumulate_dx != 0)
+ *   dW_shard   = dz^T . X          bf16 [C_shard][lddw]
+ *   db_shard   = column sums of dz fp32 [C_shard]   (skipped if NULL)
+ * dz is held once, in bf16, in the workspace.  grad_scale = 1 gives the gradient of
+ * the summed loss, 1/B that of the mean loss.  dX_partial is this shard's share of
+ * the feature gradient: the sum over shards is the full dX (what flows back over
+ * the paper's bridge layer, Section 3.2.3).  dW_shard never leaves the device that
+ * owns the shard, which is the point of splitting the layer (Section 1).
+ */
+int ws_split_fc_bwd(const void* X, int64_t ldx,
+                    const void* W_shard, int64_t ldw,
+                    const float* b_shard,
+                    const float* logsumexp,
+                    const int32_t* labels,
+                    int32_t B, int32_t D, int32_t C_shard, int32_t class_offset,
+                    float grad_scale,
+                    float* dX_partial, int64_t lddx, int32_t accumulate_dx,
+                    void* dW_shard, int64_t lddw,
+                    float* db_shard,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WHALESPLIT_H */

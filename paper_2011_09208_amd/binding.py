@@ -1,0 +1,111 @@
+"""ctypes binding over libwhalesplit.so: argument marshalling only.
+
+Every function has the name of the C entry point it calls (minus the `ws_` prefix)
+and takes torch tensors that already live on the GPU; torch is used for device
+memory and the current stream, nothing else.  There is no CPU fallback: if the
+library has not been built, importing this module raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libwhalesplit.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it with `python -m paper_2011_09208_amd.buildlib` "
+        "(or __graft_entry__.build()); there is no fallback path")
+
+lib = ctypes.CDLL(LIB_PATH)
+
+_p, _i32, _i64, _sz, _f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t, ctypes.c_float
+
+lib.ws_status_string.restype = ctypes.c_char_p
+lib.ws_status_string.argtypes = [ctypes.c_int]
+lib.ws_version.restype = ctypes.c_int
+lib.ws_version.argtypes = []
+lib.ws_fwd_workspace_bytes.restype = _sz
+lib.ws_fwd_workspace_bytes.argtypes = [_i32, _i32, _i32]
+lib.ws_bwd_workspace_bytes.restype = _sz
+lib.ws_bwd_workspace_bytes.argtypes = [_i32, _i32, _i32]
+lib.ws_split_fc_fwd.restype = ctypes.c_int
+lib.ws_split_fc_fwd.argtypes = [_p, _i64, _p, _i64, _p, _p, _i32, _i32, _i32, _i32, _p, _p, _p, _p, _sz, _p]
+lib.ws_combine_partials.restype = ctypes.c_int
+lib.ws_combine_partials.argtypes = [_p, _p, _p, _i32, _i32, _i64, _p, _p, _p, _p]
+lib.ws_split_fc_bwd.restype = ctypes.c_int
+lib.ws_split_fc_bwd.argtypes = [_p, _i64, _p, _i64, _p, _p, _p, _i32, _i32, _i32, _i32, _f32,
+                                _p, _i64, _i32, _p, _i64, _p, _p, _sz, _p]
+
+EXPORTS = ["ws_status_string", "ws_version", "ws_fwd_workspace_bytes", "ws_split_fc_fwd",
+           "ws_combine_partials", "ws_bwd_workspace_bytes", "ws_split_fc_bwd"]
+
+
+class WhaleSplitError(RuntimeError):
+    def __init__(self, status):
+        self.status = int(status)
+        super().__init__(lib.ws_status_string(self.status).decode())
+
+
+def _check(status):
+    if status != 0:
+        raise WhaleSplitError(status)
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def status_string(status):
+    return lib.ws_status_string(int(status)).decode()
+
+
+def version():
+    return lib.ws_version()
+
+
+def fwd_workspace_bytes(B, D, C_shard):
+    return lib.ws_fwd_workspace_bytes(B, D, C_shard)
+
+
+def bwd_workspace_bytes(B, D, C_shard):
+    return lib.ws_bwd_workspace_bytes(B, D, C_shard)
+
+
+def split_fc_fwd(X, W_shard, b_shard, labels, class_offset, row_max, row_sumexp, label_logit, workspace):
+    """X bf16 [B, D]; W_shard bf16 [C_shard, D]; b_shard fp32 [C_shard] or None; labels int32 [B];
+    outputs fp32 [B]; workspace uint8 of at least fwd_workspace_bytes."""
+    B, D = X.shape
+    C = W_shard.shape[0]
+    _check(lib.ws_split_fc_fwd(_ptr(X), X.stride(0), _ptr(W_shard), W_shard.stride(0), _ptr(b_shard),
+                               _ptr(labels), B, D, C, int(class_offset), _ptr(row_max), _ptr(row_sumexp),
+                               _ptr(label_logit), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                               _stream()))
+
+
+def combine_partials(row_max, row_sumexp, label_logit, logsumexp, loss_rows, loss_mean=None):
+    """Statistics are fp32 [S, B] (row pitch = stride(0)); outputs fp32 [B]; loss_mean fp32 [1] or None."""
+    S, B = row_max.shape
+    stride = row_max.stride(0) if S > 1 else max(B, row_max.stride(0))
+    assert row_sumexp.shape == row_max.shape and label_logit.shape == row_max.shape
+    if S > 1:
+        assert row_sumexp.stride(0) == stride and label_logit.stride(0) == stride
+    _check(lib.ws_combine_partials(_ptr(row_max), _ptr(row_sumexp), _ptr(label_logit), S, B, stride,
+                                   _ptr(logsumexp), _ptr(loss_rows), _ptr(loss_mean), _stream()))
+
+
+def split_fc_bwd(X, W_shard, b_shard, logsumexp, labels, class_offset, grad_scale, dX_partial, accumulate_dx,
+                 dW_shard, db_shard, workspace):
+    """dX_partial fp32 [B, D]; dW_shard bf16 [C_shard, D]; db_shard fp32 [C_shard] or None."""
+    B, D = X.shape
+    C = W_shard.shape[0]
+    _check(lib.ws_split_fc_bwd(_ptr(X), X.stride(0), _ptr(W_shard), W_shard.stride(0), _ptr(b_shard),
+                               _ptr(logsumexp), _ptr(labels), B, D, C, int(class_offset), float(grad_scale),
+                               _ptr(dX_partial), dX_partial.stride(0), int(bool(accumulate_dx)),
+                               _ptr(dW_shard), dW_shard.stride(0), _ptr(db_shard), _ptr(workspace),
+                               workspace.numel() * workspace.element_size(), _stream()))

@@ -1,0 +1,227 @@
+// Shared bf16 MFMA GEMM main loop for gfx950 (MI355X), used by all four contractions
+// of the split fully-connected head.
+//
+// One workgroup of 512 threads (8 wave64s, two per SIMD) owns a 256 x 256 output tile
+// and walks the contraction in steps of 64.  The waves form a 2 (M) x 4 (N) grid; each
+// owns a 128 x 64 sub-tile held as 4 x 2 accumulators of v_mfma_f32_32x32x16_bf16.
+//
+// An operand tile is staged in LDS in one of two layouts, chosen by how the operand
+// lies in memory relative to the contraction index k:
+//   KC ("k contiguous"): memory is [row][k]; LDS holds [256 rows][64 k] (128 B per row,
+//       16-byte chunks XOR-swizzled by (row >> 1) & 7); a lane's MFMA fragment (8
+//       consecutive k of one row) is one ds_read_b128.
+//   KS ("k strided"):    memory is [k][col]; LDS holds [64 k][256 cols] (512 B per k-row,
+//       16-byte chunks XOR-swizzled by (k & 3) << 2); the fragment is gathered with two
+//       ds_read_b64_tr_b16 transpose reads (4 consecutive k of one column each).
+// Lane layouts used (checked on the hardware): for v_mfma_f32_32x32x16_bf16 lane l
+// supplies row l % 32, k = 8 * (l / 32) .. + 7 of either operand; accumulator register v
+// of lane l is element (8 * (v / 4) + 4 * (l / 32) + v % 4, l % 32).  ds_read_b64_tr_b16
+// works on blocks of 16 lanes: lane i of a block receives, as element e, the (i % 4)-th
+// 16-bit value of the 8 bytes addressed by lane 4 * e + i / 4 of the same block.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ws {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+
+constexpr int TILE_M = 256;
+constexpr int TILE_N = 256;
+constexpr int TILE_K = 64;
+constexpr int NTHREADS = 512;
+constexpr int WAVE_M = 128;     // rows of the output tile one wave owns
+constexpr int WAVE_N = 64;
+constexpr int MT = WAVE_M / 32; // 32 x 32 MFMA tiles per wave along M
+constexpr int NT = WAVE_N / 32;
+constexpr int OPERAND_TILE_BYTES = 256 * TILE_K * 2;           // 32 KiB
+constexpr int STAGE_BYTES = 2 * OPERAND_TILE_BYTES;            // A + B
+constexpr int LDS_BYTES = 2 * STAGE_BYTES;                     // double buffered: 128 KiB
+
+enum { KC = 0, KS = 1 };
+
+// Description of one GEMM operand in global memory (16-bit elements).
+//   KC: element (row, k) at base[row * ld + k];  `row_max` = last valid row (rows beyond are
+//       clamped to it, so the loads stay in bounds and the caller masks the results).
+//   KS: element (k, col) at base[k * ld + col];  `k_max` = last valid k-row (clamped; the
+//       other operand must be zero there), `col_max8` = last valid 8-element chunk start.
+struct Operand {
+    const uint16_t* base;
+    int64_t ld;
+    int lim0;   // KC: row_max      KS: k_max
+    int lim1;   // KC: unused       KS: col_max8
+};
+
+// ---- global -> registers -> LDS staging ---------------------------------------------------
+
+template <int KIND>
+__device__ __forceinline__ void tile_g2r(u32x4 (&st)[4], const Operand& op, int o0, int k0, int tid) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int q = tid + NTHREADS * j;
+        if (KIND == KC) {
+            const int row = q >> 3, ch = q & 7;
+            int r = o0 + row;
+            r = r < op.lim0 ? r : op.lim0;
+            st[j] = *reinterpret_cast<const u32x4*>(op.base + (int64_t)r * op.ld + k0 + ch * 8);
+        } else {
+            const int kr = q >> 5, ch = q & 31;
+            int k = k0 + kr;
+            k = k < op.lim0 ? k : op.lim0;
+            int c = o0 + ch * 8;
+            c = c < op.lim1 ? c : op.lim1;
+            st[j] = *reinterpret_cast<const u32x4*>(op.base + (int64_t)k * op.ld + c);
+        }
+    }
+}
+
+template <int KIND>
+__device__ __forceinline__ void tile_r2s(char* lds, const u32x4 (&st)[4], int tid) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int q = tid + NTHREADS * j;
+        int off;
+        if (KIND == KC) {
+            const int row = q >> 3, ch = q & 7;
+            off = row * 128 + ((ch ^ ((row >> 1) & 7)) << 4);
+        } else {
+            const int kr = q >> 5, ch = q & 31;
+            off = kr * 512 + ((ch ^ ((kr & 3) << 2)) << 4);
+        }
+        *reinterpret_cast<u32x4*>(lds + off) = st[j];
+    }
+}
+
+// ---- LDS -> MFMA fragments ------------------------------------------------------------------
+
+// Per-lane byte offsets into an operand tile, computed once per kernel.
+template <int KIND, int NTILES>
+struct FragAddr {
+    int off[KIND == KC ? 4 : NTILES];   // KC: one per k-substep; KS: one per 32-wide tile
+
+    // `w0` = first row/column of this wave's sub-tile inside the 256-wide operand tile.
+    __device__ __forceinline__ void init(int lane, int w0) {
+        if (KIND == KC) {
+            const int r = lane & 31, h = lane >> 5;
+            const int sw = (r >> 1) & 7;            // w0 and 32 * t are multiples of 32: no effect on the swizzle
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) off[ks] = (w0 + r) * 128 + (((2 * ks + h) ^ sw) << 4);
+        } else {
+            const int x = (lane & 15) >> 2;          // k-row within the group of four == (k & 3)
+            const int krow = 8 * (lane >> 5) + x;
+#pragma unroll
+            for (int t = 0; t < NTILES; ++t) {
+                const int col = w0 + 32 * t + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+                const int ch = col >> 3;
+                off[t] = krow * 512 + ((ch ^ (x << 2)) << 4) + ((col & 7) << 1);
+            }
+        }
+    }
+
+    // Fragment of 32-wide tile t for k-substep ks (16 k each) from the operand tile at `lds`.
+    __device__ __forceinline__ bf16x8 load(const char* lds, int t, int ks) const {
+        if (KIND == KC) {
+            return *reinterpret_cast<const bf16x8*>(lds + off[ks] + t * (32 * 128));
+        } else {
+            typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
+            const char* p = lds + off[t] + ks * (16 * 512);
+            s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p));
+            s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 4 * 512));
+            s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            return __builtin_bit_cast(bf16x8, v);
+        }
+    }
+};
+
+// ---- main loop ---------------------------------------------------------------------------------
+
+// acc[mt][nt] += A(m0 .. m0+255, k) * B(n0 .. n0+255, k) for k in [k_begin, k_begin + 64 * k_steps).
+// For a KC operand o0 is its first row; for a KS operand its first column.
+// Ends with a workgroup barrier, so LDS may be reused by the caller right away.
+template <int AKIND, int BKIND>
+__device__ __forceinline__ void gemm_mainloop(f32x16 (&acc)[MT][NT], const Operand& A, const Operand& Bop,
+                                              int m0, int n0, int k_begin, int k_steps, char* lds) {
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave >> 2, wn = wave & 3;
+
+    FragAddr<AKIND, MT> fa;
+    FragAddr<BKIND, NT> fb;
+    fa.init(lane, wm * WAVE_M);
+    fb.init(lane, wn * WAVE_N);
+
+    u32x4 sa[4], sb[4];
+    tile_g2r<AKIND>(sa, A, m0, k_begin, tid);
+    tile_g2r<BKIND>(sb, Bop, n0, k_begin, tid);
+    tile_r2s<AKIND>(lds, sa, tid);
+    tile_r2s<BKIND>(lds + OPERAND_TILE_BYTES, sb, tid);
+    __syncthreads();
+
+    for (int kt = 0; kt < k_steps; ++kt) {
+        const bool more = kt + 1 < k_steps;
+        if (more) {
+            const int k0 = k_begin + (kt + 1) * TILE_K;
+            tile_g2r<AKIND>(sa, A, m0, k0, tid);
+            tile_g2r<BKIND>(sb, Bop, n0, k0, tid);
+        }
+        const char* la = lds + (kt & 1) * STAGE_BYTES;
+        const char* lb = la + OPERAND_TILE_BYTES;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            bf16x8 af[MT], bfr[NT];
+#pragma unroll
+            for (int t = 0; t < MT; ++t) af[t] = fa.load(la, t, ks);
+#pragma unroll
+            for (int t = 0; t < NT; ++t) bfr[t] = fb.load(lb, t, ks);
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+#pragma unroll
+                for (int j = 0; j < NT; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        }
+        if (more) {
+            char* ls = lds + ((kt + 1) & 1) * STAGE_BYTES;
+            tile_r2s<AKIND>(ls, sa, tid);
+            tile_r2s<BKIND>(ls + OPERAND_TILE_BYTES, sb, tid);
+        }
+        __syncthreads();
+    }
+}
+
+__device__ __forceinline__ void zero_acc(f32x16 (&acc)[MT][NT]) {
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+}
+
+// Workgroups are handed to the 8 XCDs round-robin by their linear id; each XCD has its own L2.
+// Map the hardware id to a logical tile id so that each XCD walks one contiguous range of
+// logical tiles (tiles that share an operand panel are numbered next to each other).
+// The grid must hold 8 * ceil(n_tiles / 8) workgroups; returns -1 for the surplus ones.
+__device__ __forceinline__ int xcd_logical_tile(int n_tiles) {
+    const int per = (n_tiles + 7) >> 3;
+    const int bid = blockIdx.x;
+    const int t = (bid & 7) * per + (bid >> 3);
+    return t < n_tiles ? t : -1;
+}
+
+// Round-to-nearest-even conversion of two floats to a packed bf16 pair.
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+    f32x2 f = {a, b};
+    bf16x2 r = __builtin_convertvector(f, bf16x2);
+    return __builtin_bit_cast(uint32_t, r);
+}
+
+}  // namespace ws

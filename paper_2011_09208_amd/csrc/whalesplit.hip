@@ -1,0 +1,583 @@
+// libwhalesplit: kernels and C-ABI entry points (see include/whalesplit.h for the contract).
+//
+// Kernels, in the order one training step of a shard runs them:
+//   fwd_logits_stats   z^T tile = W_s . X^T on the matrix cores; per-row max / sum-exp / label
+//                      logit reduced in the epilogue; one (max, sum) partial per 256-class tile
+//   merge_class_tiles  merges those partials into row_max / row_sumexp of the shard
+//   combine_partials   merges the shards' statistics into logsumexp and loss
+//   bwd_recompute_dz   same GEMM again, epilogue dz = g (exp(z - lse) - onehot) stored as bf16
+//   colsum_db          db = column sums of dz
+//   bwd_dx             dX_partial = dz . W_s, split along the class contraction; partial sums
+//   reduce_dx          sums the split-K partials (optionally accumulating into the caller's dX)
+//   bwd_dw             dW_s = dz^T . X
+#include <hip/hip_runtime.h>
+#include <limits.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "../../include/whalesplit.h"
+#include "gemm_core.h"
+
+namespace ws {
+
+constexpr float NEG_INF = -INFINITY;
+
+__device__ __forceinline__ float xor32(float v) { return __shfl_xor(v, 32, 64); }
+
+// Merge of two (max, sum-exp) pairs; either may be the empty pair (-inf, 0).
+__device__ __forceinline__ void merge_ms(float& m, float& s, float m2, float s2) {
+    const float M = fmaxf(m, m2);
+    const float f1 = (m == NEG_INF) ? 0.0f : __expf(m - M);
+    const float f2 = (m2 == NEG_INF) ? 0.0f : __expf(m2 - M);
+    s = s * f1 + s2 * f2;
+    m = M;
+}
+
+// Class id (relative to the wave's first class) held in accumulator register v of M-tile mt.
+__device__ __forceinline__ int acc_row(int mt, int v, int h) { return 32 * mt + 8 * (v >> 2) + 4 * h + (v & 3); }
+
+// z = acc + bias, with classes beyond the shard set to -inf.  `c_rel0` = the wave's first class
+// relative to the workgroup's tile, `c_left` = number of valid classes from the wave's first class.
+__device__ __forceinline__ void add_bias_and_mask(f32x16 (&acc)[MT][NT], const float* sbias, bool has_bias,
+                                                  int c_rel0, int c_left, int h) {
+    if (has_bias) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int v4 = 0; v4 < 4; ++v4) {
+                const f32x4 b4 = *reinterpret_cast<const f32x4*>(sbias + c_rel0 + 32 * mt + 8 * v4 + 4 * h);
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt) acc[mt][nt][4 * v4 + e] += b4[e];
+            }
+    }
+    if (c_left < WAVE_M) {   // wave-uniform: only the ragged last class tile pays for masking
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                if (acc_row(mt, v, h) >= c_left) {
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt) acc[mt][nt][v] = NEG_INF;
+                }
+    }
+}
+
+struct FcArgs {
+    const uint16_t* X; int64_t ldx;
+    const uint16_t* W; int64_t ldw;
+    const float* bias;
+    const int32_t* labels;
+    int B, D, C, class_offset;
+    int Bpad;        // B rounded up to 256
+    int nBT, nCT;    // tiles along the batch and class dimensions
+};
+
+// Runs the logits GEMM of one 256-class x 256-row tile and leaves z (bias added, padding = -inf)
+// in acc.  M = classes (A = W_s, KC), N = batch rows (B operand = X, KC), K = D.
+__device__ __forceinline__ void logits_tile(f32x16 (&acc)[MT][NT], const FcArgs& a, int ct, int bt, char* lds,
+                                            float* sbias) {
+    zero_acc(acc);
+    Operand A{a.W, a.ldw, a.C - 1, 0};
+    Operand Bo{a.X, a.ldx, a.B - 1, 0};
+    gemm_mainloop<KC, KC>(acc, A, Bo, ct * TILE_M, bt * TILE_N, 0, a.D / TILE_K, lds);
+    const int tid = threadIdx.x;
+    const bool has_bias = a.bias != nullptr;
+    if (has_bias) {
+        if (tid < TILE_M) {
+            const int c = ct * TILE_M + tid;
+            sbias[tid] = c < a.C ? a.bias[c] : 0.0f;
+        }
+        __syncthreads();
+    }
+    const int wm = (tid >> 6) >> 2;
+    add_bias_and_mask(acc, sbias, has_bias, wm * WAVE_M, a.C - (ct * TILE_M + wm * WAVE_M), (tid & 63) >> 5);
+}
+
+__global__ __launch_bounds__(NTHREADS) void fwd_logits_stats(FcArgs a, float* __restrict__ part_max,
+                                                              float* __restrict__ part_sum,
+                                                              float* __restrict__ label_logit) {
+    __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
+    const int tile = xcd_logical_tile(a.nBT * a.nCT);
+    if (tile < 0) return;
+    const int ct = tile / a.nBT, bt = tile % a.nBT;   // batch tiles fastest: neighbours share the W panel
+    float* sbias = reinterpret_cast<float*>(lds);          // reused after the main loop
+    float* red_m = reinterpret_cast<float*>(lds) + 256;    // [2][256]
+    float* red_s = red_m + 512;
+
+    f32x16 acc[MT][NT];
+    logits_tile(acc, a, ct, bt, lds, sbias);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 2, wn = wave & 3, h = lane >> 5, jl = lane & 31;
+    const int cw0 = ct * TILE_M + wm * WAVE_M;           // first class of this wave (shard-local)
+
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int row = bt * TILE_N + wn * WAVE_N + 32 * nt + jl;
+        float mx = NEG_INF;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) mx = fmaxf(mx, acc[mt][nt][v]);
+        const float ms = (mx == NEG_INF) ? 0.0f : mx;
+        float s = 0.0f;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) s += __expf(acc[mt][nt][v] - ms);
+        merge_ms(mx, s, xor32(mx), xor32(s));            // the other half-wave holds the other classes of this row
+        if (h == 0) {
+            red_m[wm * 256 + wn * WAVE_N + 32 * nt + jl] = mx;
+            red_s[wm * 256 + wn * WAVE_N + 32 * nt + jl] = s;
+        }
+
+        // Label logit.  Exactly one lane of the whole grid holds z[row][label - offset] when the label
+        // lies in the shard; rows whose label lies outside get 0 from the first class tile.
+        const bool row_ok = row < a.B;
+        const int local = row_ok ? a.labels[row] - a.class_offset : -1;
+        const bool in_shard = local >= 0 && local < a.C;
+        const int rel = local - cw0;
+        const bool mine = in_shard && rel >= 0 && rel < WAVE_M && (((rel & 31) >> 2) & 1) == h;
+        if (__any(mine)) {
+            float t = 0.0f;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    if (acc_row(mt, v, h) == rel) t = acc[mt][nt][v];
+            if (mine) label_logit[row] = t;
+        }
+        if (ct == 0 && wm == 0 && h == 0 && row_ok && !in_shard) label_logit[row] = 0.0f;
+    }
+    __syncthreads();
+    if (tid < 256) {
+        float m = red_m[tid], s = red_s[tid];
+        merge_ms(m, s, red_m[256 + tid], red_s[256 + tid]);
+        const int64_t o = (int64_t)ct * a.Bpad + bt * TILE_N + tid;
+        part_max[o] = m;
+        part_sum[o] = s;
+    }
+}
+
+__global__ void merge_class_tiles(const float* __restrict__ part_max, const float* __restrict__ part_sum,
+                                  int nCT, int Bpad, int B, float* __restrict__ row_max,
+                                  float* __restrict__ row_sumexp) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= B) return;
+    float m = NEG_INF;
+    for (int t = 0; t < nCT; ++t) m = fmaxf(m, part_max[(int64_t)t * Bpad + i]);
+    float s = 0.0f;
+    for (int t = 0; t < nCT; ++t) {
+        const float mt = part_max[(int64_t)t * Bpad + i];
+        if (mt != NEG_INF) s += part_sum[(int64_t)t * Bpad + i] * __expf(mt - m);
+    }
+    row_max[i] = m;
+    row_sumexp[i] = s;
+}
+
+__global__ void combine_partials_kernel(const float* __restrict__ row_max, const float* __restrict__ row_sumexp,
+                                        const float* __restrict__ label_logit, int S, int B, int64_t stride,
+                                        float* __restrict__ logsumexp, float* __restrict__ loss_rows) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= B) return;
+    float m = NEG_INF;
+    for (int s = 0; s < S; ++s) m = fmaxf(m, row_max[s * stride + i]);
+    float tot = 0.0f, t = 0.0f;
+    for (int s = 0; s < S; ++s) {
+        const float ms = row_max[s * stride + i];
+        if (ms != NEG_INF) tot += row_sumexp[s * stride + i] * __expf(ms - m);
+        t += label_logit[s * stride + i];
+    }
+    const float lse = m + __logf(tot);
+    logsumexp[i] = lse;
+    loss_rows[i] = lse - t;
+}
+
+// Mean of loss_rows in a fixed summation order (one workgroup).
+__global__ __launch_bounds__(1024) void mean_loss_kernel(const float* __restrict__ loss_rows, int B,
+                                                          float* __restrict__ loss_mean) {
+    __shared__ float red[1024];
+    float acc = 0.0f;
+    for (int i = threadIdx.x; i < B; i += 1024) acc += loss_rows[i];
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    for (int w = 512; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *loss_mean = red[0] / (float)B;
+}
+
+__global__ __launch_bounds__(NTHREADS) void bwd_recompute_dz(FcArgs a, const float* __restrict__ logsumexp,
+                                                              float grad_scale, uint16_t* __restrict__ dZ,
+                                                              int64_t ldz) {
+    __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
+    const int tile = xcd_logical_tile(a.nBT * a.nCT);
+    if (tile < 0) return;
+    const int ct = tile / a.nBT, bt = tile % a.nBT;
+    float* sbias = reinterpret_cast<float*>(lds);
+
+    f32x16 acc[MT][NT];
+    logits_tile(acc, a, ct, bt, lds, sbias);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 2, wn = wave & 3, h = lane >> 5, jl = lane & 31;
+    const int cw0 = ct * TILE_M + wm * WAVE_M;
+
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int row = bt * TILE_N + wn * WAVE_N + 32 * nt + jl;     // < Bpad: dZ has that many rows
+        const bool row_ok = row < a.B;
+        const float lse = row_ok ? logsumexp[row] : 0.0f;
+        const float g = row_ok ? grad_scale : 0.0f;                    // padded rows store exact zeros
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mt][nt][v] = g * __expf(acc[mt][nt][v] - lse);   // exp(-inf) = 0 on padded classes
+
+        const int local = row_ok ? a.labels[row] - a.class_offset : -1;
+        const bool in_shard = local >= 0 && local < a.C;
+        const int rel = local - cw0;
+        const bool mine = in_shard && rel >= 0 && rel < WAVE_M && (((rel & 31) >> 2) & 1) == h;
+        if (__any(mine)) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    if (mine && acc_row(mt, v, h) == rel) acc[mt][nt][v] -= g;
+        }
+        uint16_t* zrow = dZ + (int64_t)row * ldz + cw0 + 4 * h;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int v4 = 0; v4 < 4; ++v4) {
+                u32x2 p;
+                p[0] = pack_bf16(acc[mt][nt][4 * v4 + 0], acc[mt][nt][4 * v4 + 1]);
+                p[1] = pack_bf16(acc[mt][nt][4 * v4 + 2], acc[mt][nt][4 * v4 + 3]);
+                *reinterpret_cast<u32x2*>(zrow + 32 * mt + 8 * v4) = p;
+            }
+    }
+}
+
+// db[c] = sum over rows of dz[row][c].  A workgroup owns 128 columns; thread (tx, ty) sums four
+// columns over rows ty, ty + 8, ...; the eight row groups are then added through LDS.
+__global__ __launch_bounds__(256) void colsum_db(const uint16_t* __restrict__ dZ, int64_t ldz, int B, int C,
+                                                  float* __restrict__ db) {
+    __shared__ float red[8][128];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const int c0 = blockIdx.x * 128 + tx * 4;
+    float s[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int r = ty; r < B; r += 8) {
+        const u32x2 p = *reinterpret_cast<const u32x2*>(dZ + (int64_t)r * ldz + c0);
+        s[0] += __uint_as_float(p[0] << 16);
+        s[1] += __uint_as_float(p[0] & 0xffff0000u);
+        s[2] += __uint_as_float(p[1] << 16);
+        s[3] += __uint_as_float(p[1] & 0xffff0000u);
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) red[ty][tx * 4 + e] = s[e];
+    __syncthreads();
+    if (threadIdx.x < 128) {
+        float t = 0.0f;
+#pragma unroll
+        for (int y = 0; y < 8; ++y) t += red[y][threadIdx.x];
+        const int c = blockIdx.x * 128 + threadIdx.x;
+        if (c < C) db[c] = t;
+    }
+}
+
+struct DxArgs {
+    const uint16_t* dZ; int64_t ldz;     // [Bpad][Cpad]
+    const uint16_t* W; int64_t ldw;      // [C][D]
+    int B, D, C;
+    int Bpad;
+    int nDT, nBT, splits, steps_per_split, steps_total;
+    float* out; int64_t ldo; int64_t split_stride;   // out[split][b][d]
+};
+
+// dX^T tile: M = features d (A = W_s read k-strided), N = batch rows (B operand = dz, k contiguous),
+// K = the shard's classes, cut into `splits` ranges.
+__global__ __launch_bounds__(NTHREADS) void bwd_dx(DxArgs a) {
+    __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
+    const int tile = xcd_logical_tile(a.nDT * a.nBT * a.splits);
+    if (tile < 0) return;
+    const int bt = tile % a.nBT;
+    const int dt = (tile / a.nBT) % a.nDT;
+    const int sp = tile / (a.nBT * a.nDT);
+    const int s0 = sp * a.steps_per_split;
+    int ns = a.steps_total - s0;
+    ns = ns < a.steps_per_split ? ns : a.steps_per_split;
+
+    f32x16 acc[MT][NT];
+    zero_acc(acc);
+    Operand A{a.W, a.ldw, a.C - 1, a.D - 8};
+    Operand Bo{a.dZ, a.ldz, a.Bpad - 1, 0};
+    gemm_mainloop<KS, KC>(acc, A, Bo, dt * TILE_M, bt * TILE_N, s0 * TILE_K, ns, lds);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 2, wn = wave & 3, h = lane >> 5, jl = lane & 31;
+    float* out = a.out + sp * a.split_stride;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int row = bt * TILE_N + wn * WAVE_N + 32 * nt + jl;
+        if (row >= a.B) continue;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int v4 = 0; v4 < 4; ++v4) {
+                const int d = dt * TILE_M + wm * WAVE_M + 32 * mt + 8 * v4 + 4 * h;
+                if (d < a.D) {
+                    f32x4 o = {acc[mt][nt][4 * v4], acc[mt][nt][4 * v4 + 1], acc[mt][nt][4 * v4 + 2],
+                               acc[mt][nt][4 * v4 + 3]};
+                    *reinterpret_cast<f32x4*>(out + (int64_t)row * a.ldo + d) = o;
+                }
+            }
+    }
+}
+
+__global__ void reduce_dx(const float* __restrict__ parts, int splits, int64_t split_stride, int B, int D,
+                          float* __restrict__ dX, int64_t lddx, int accumulate) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // one float4 per thread
+    const int d4 = D >> 2;
+    if (i >= (int64_t)B * d4) return;
+    const int row = (int)(i / d4), d = (int)(i % d4) * 4;
+    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+    for (int p = 0; p < splits; ++p) s += *reinterpret_cast<const f32x4*>(parts + p * split_stride + (int64_t)row * D + d);
+    float* o = dX + (int64_t)row * lddx + d;
+    if (accumulate) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] += s[e];
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = s[e];
+    }
+}
+
+struct DwArgs {
+    const uint16_t* X; int64_t ldx;      // [B][D]
+    const uint16_t* dZ; int64_t ldz;     // [Bpad][Cpad]
+    int B, D, C;
+    int nDT, nCT, k_steps;
+    uint16_t* dW; int64_t lddw;
+};
+
+// dW^T tile: M = features d (A = X read k-strided), N = classes (B operand = dz read k-strided),
+// K = batch rows.
+__global__ __launch_bounds__(NTHREADS) void bwd_dw(DwArgs a) {
+    __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
+    const int tile = xcd_logical_tile(a.nDT * a.nCT);
+    if (tile < 0) return;
+    const int dt = tile % a.nDT, ct = tile / a.nDT;    // feature tiles fastest: neighbours share the dz panel
+
+    f32x16 acc[MT][NT];
+    zero_acc(acc);
+    Operand A{a.X, a.ldx, a.B - 1, a.D - 8};
+    Operand Bo{a.dZ, a.ldz, INT_MAX, INT_MAX};         // dz is padded to whole tiles: never clamped
+    gemm_mainloop<KS, KS>(acc, A, Bo, dt * TILE_M, ct * TILE_N, 0, a.k_steps, lds);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 2, wn = wave & 3, h = lane >> 5, jl = lane & 31;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int c = ct * TILE_N + wn * WAVE_N + 32 * nt + jl;
+        if (c >= a.C) continue;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int v4 = 0; v4 < 4; ++v4) {
+                const int d = dt * TILE_M + wm * WAVE_M + 32 * mt + 8 * v4 + 4 * h;
+                if (d < a.D) {
+                    u32x2 p;
+                    p[0] = pack_bf16(acc[mt][nt][4 * v4 + 0], acc[mt][nt][4 * v4 + 1]);
+                    p[1] = pack_bf16(acc[mt][nt][4 * v4 + 2], acc[mt][nt][4 * v4 + 3]);
+                    *reinterpret_cast<u32x2*>(a.dW + (int64_t)c * a.lddw + d) = p;
+                }
+            }
+    }
+}
+
+// ---- host side -----------------------------------------------------------------------------------
+
+static inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
+static inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+static inline int xcd_grid(int n_tiles) { return 8 * ((n_tiles + 7) / 8); }
+
+struct BwdPlan {
+    int64_t Bpad, Cpad;
+    int nBT, nCT, nDT;
+    int steps_total, splits, steps_per_split;
+    size_t dz_bytes, parts_bytes;
+};
+
+static bool shape_ok(int32_t B, int32_t D, int32_t C) { return B > 0 && D > 0 && C > 0 && D % 64 == 0; }
+
+static BwdPlan plan_bwd(int32_t B, int32_t D, int32_t C) {
+    BwdPlan p;
+    p.Bpad = round_up(B, 256);
+    p.Cpad = round_up(C, 256);
+    p.nBT = (int)(p.Bpad / 256);
+    p.nCT = (int)(p.Cpad / 256);
+    p.nDT = (int)(round_up(D, 256) / 256);
+    p.steps_total = (int)(round_up(C, TILE_K) / TILE_K);
+    const int tiles = p.nDT * p.nBT;
+    int want = tiles >= 256 ? 1 : (256 + tiles - 1) / tiles;     // fill the 256 CUs once
+    if (want > p.steps_total) want = p.steps_total;
+    p.steps_per_split = (p.steps_total + want - 1) / want;
+    p.splits = (p.steps_total + p.steps_per_split - 1) / p.steps_per_split;
+    p.dz_bytes = (size_t)p.Bpad * p.Cpad * 2;
+    p.parts_bytes = (size_t)p.splits * B * D * 4;
+    return p;
+}
+
+static size_t fwd_bytes(int32_t B, int32_t C) {
+    return (size_t)2 * (round_up(C, 256) / 256) * round_up(B, 256) * sizeof(float);
+}
+
+static int check_fc_common(const void* X, int64_t ldx, const void* W, int64_t ldw, const float* bias,
+                           const int32_t* labels, int32_t B, int32_t D, int32_t C, int32_t class_offset) {
+    if (!X || !W || !labels) return WS_ERR_NULL;
+    if (!shape_ok(B, D, C)) return WS_ERR_SHAPE;
+    if (ldx < D || ldw < D) return WS_ERR_SHAPE;
+    if (class_offset < 0 || (int64_t)class_offset + C > INT32_MAX) return WS_ERR_RANGE;
+    if (!aligned(X, 16) || !aligned(W, 16) || ldx % 8 || ldw % 8) return WS_ERR_ALIGN;
+    if (!aligned(labels, 4) || (bias && !aligned(bias, 4))) return WS_ERR_ALIGN;
+    return WS_OK;
+}
+
+static int launch_status() { return hipGetLastError() == hipSuccess ? WS_OK : WS_ERR_HIP; }
+
+}  // namespace ws
+
+using namespace ws;
+
+extern "C" {
+
+const char* ws_status_string(int status) {
+    switch (status) {
+        case WS_OK: return "WS_OK";
+        case WS_ERR_NULL: return "WS_ERR_NULL";
+        case WS_ERR_SHAPE: return "WS_ERR_SHAPE";
+        case WS_ERR_ALIGN: return "WS_ERR_ALIGN";
+        case WS_ERR_RANGE: return "WS_ERR_RANGE";
+        case WS_ERR_WORKSPACE: return "WS_ERR_WORKSPACE";
+        case WS_ERR_HIP: return "WS_ERR_HIP";
+        default: return "WS_ERR_UNKNOWN";
+    }
+}
+
+int ws_version(void) { return 1000; }
+
+size_t ws_fwd_workspace_bytes(int32_t B, int32_t D, int32_t C_shard) {
+    return shape_ok(B, D, C_shard) ? fwd_bytes(B, C_shard) : 0;
+}
+
+size_t ws_bwd_workspace_bytes(int32_t B, int32_t D, int32_t C_shard) {
+    if (!shape_ok(B, D, C_shard)) return 0;
+    const BwdPlan p = plan_bwd(B, D, C_shard);
+    return p.dz_bytes + p.parts_bytes;
+}
+
+int ws_split_fc_fwd(const void* X, int64_t ldx, const void* W_shard, int64_t ldw, const float* b_shard,
+                    const int32_t* labels, int32_t B, int32_t D, int32_t C_shard, int32_t class_offset,
+                    float* row_max, float* row_sumexp, float* label_logit, void* workspace,
+                    size_t workspace_bytes, void* stream) {
+    if (!row_max || !row_sumexp || !label_logit) return WS_ERR_NULL;
+    int st = check_fc_common(X, ldx, W_shard, ldw, b_shard, labels, B, D, C_shard, class_offset);
+    if (st != WS_OK) return st;
+    if (!aligned(row_max, 4) || !aligned(row_sumexp, 4) || !aligned(label_logit, 4)) return WS_ERR_ALIGN;
+    if (!workspace || workspace_bytes < fwd_bytes(B, C_shard)) return WS_ERR_WORKSPACE;
+    if (!aligned(workspace, 16)) return WS_ERR_ALIGN;
+
+    FcArgs a;
+    a.X = static_cast<const uint16_t*>(X); a.ldx = ldx;
+    a.W = static_cast<const uint16_t*>(W_shard); a.ldw = ldw;
+    a.bias = b_shard; a.labels = labels;
+    a.B = B; a.D = D; a.C = C_shard; a.class_offset = class_offset;
+    a.Bpad = (int)round_up(B, 256);
+    a.nBT = a.Bpad / 256;
+    a.nCT = (int)(round_up(C_shard, 256) / 256);
+    float* part_max = static_cast<float*>(workspace);
+    float* part_sum = part_max + (size_t)a.nCT * a.Bpad;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(fwd_logits_stats, dim3(xcd_grid(a.nBT * a.nCT)), dim3(NTHREADS), 0, s, a, part_max,
+                       part_sum, label_logit);
+    hipLaunchKernelGGL(merge_class_tiles, dim3((B + 255) / 256), dim3(256), 0, s, part_max, part_sum, a.nCT,
+                       a.Bpad, B, row_max, row_sumexp);
+    return launch_status();
+}
+
+int ws_combine_partials(const float* row_max, const float* row_sumexp, const float* label_logit, int32_t S,
+                        int32_t B, int64_t shard_stride, float* logsumexp, float* loss_rows, float* loss_mean,
+                        void* stream) {
+    if (!row_max || !row_sumexp || !label_logit || !logsumexp || !loss_rows) return WS_ERR_NULL;
+    if (B <= 0 || shard_stride < B) return WS_ERR_SHAPE;
+    if (S < 1 || S > 65536) return WS_ERR_RANGE;
+    if (!aligned(row_max, 4) || !aligned(row_sumexp, 4) || !aligned(label_logit, 4) || !aligned(logsumexp, 4) ||
+        !aligned(loss_rows, 4) || (loss_mean && !aligned(loss_mean, 4)))
+        return WS_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(combine_partials_kernel, dim3((B + 255) / 256), dim3(256), 0, s, row_max, row_sumexp,
+                       label_logit, S, B, shard_stride, logsumexp, loss_rows);
+    if (loss_mean) hipLaunchKernelGGL(mean_loss_kernel, dim3(1), dim3(1024), 0, s, loss_rows, B, loss_mean);
+    return launch_status();
+}
+
+int ws_split_fc_bwd(const void* X, int64_t ldx, const void* W_shard, int64_t ldw, const float* b_shard,
+                    const float* logsumexp, const int32_t* labels, int32_t B, int32_t D, int32_t C_shard,
+                    int32_t class_offset, float grad_scale, float* dX_partial, int64_t lddx,
+                    int32_t accumulate_dx, void* dW_shard, int64_t lddw, float* db_shard, void* workspace,
+                    size_t workspace_bytes, void* stream) {
+    if (!logsumexp || !dX_partial || !dW_shard) return WS_ERR_NULL;
+    int st = check_fc_common(X, ldx, W_shard, ldw, b_shard, labels, B, D, C_shard, class_offset);
+    if (st != WS_OK) return st;
+    if (lddx < D || lddw < D) return WS_ERR_SHAPE;
+    if (!aligned(dX_partial, 16) || !aligned(dW_shard, 16) || lddx % 4 || lddw % 8) return WS_ERR_ALIGN;
+    if (!aligned(logsumexp, 4) || (db_shard && !aligned(db_shard, 4))) return WS_ERR_ALIGN;
+    const BwdPlan p = plan_bwd(B, D, C_shard);
+    if (!workspace || workspace_bytes < p.dz_bytes + p.parts_bytes) return WS_ERR_WORKSPACE;
+    if (!aligned(workspace, 16)) return WS_ERR_ALIGN;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint16_t* dZ = static_cast<uint16_t*>(workspace);
+    float* parts = reinterpret_cast<float*>(static_cast<char*>(workspace) + p.dz_bytes);
+
+    FcArgs a;
+    a.X = static_cast<const uint16_t*>(X); a.ldx = ldx;
+    a.W = static_cast<const uint16_t*>(W_shard); a.ldw = ldw;
+    a.bias = b_shard; a.labels = labels;
+    a.B = B; a.D = D; a.C = C_shard; a.class_offset = class_offset;
+    a.Bpad = (int)p.Bpad; a.nBT = p.nBT; a.nCT = p.nCT;
+    hipLaunchKernelGGL(bwd_recompute_dz, dim3(xcd_grid(p.nBT * p.nCT)), dim3(NTHREADS), 0, s, a, logsumexp,
+                       grad_scale, dZ, p.Cpad);
+    if (db_shard)
+        hipLaunchKernelGGL(colsum_db, dim3((unsigned)(p.Cpad / 128)), dim3(256), 0, s, dZ, p.Cpad, B, C_shard,
+                           db_shard);
+
+    DxArgs x;
+    x.dZ = dZ; x.ldz = p.Cpad; x.W = a.W; x.ldw = ldw;
+    x.B = B; x.D = D; x.C = C_shard; x.Bpad = (int)p.Bpad;
+    x.nDT = p.nDT; x.nBT = p.nBT; x.splits = p.splits; x.steps_per_split = p.steps_per_split;
+    x.steps_total = p.steps_total;
+    const bool direct = p.splits == 1 && !accumulate_dx;
+    x.out = direct ? dX_partial : parts;
+    x.ldo = direct ? lddx : D;
+    x.split_stride = (int64_t)B * D;
+    hipLaunchKernelGGL(bwd_dx, dim3(xcd_grid(p.nDT * p.nBT * p.splits)), dim3(NTHREADS), 0, s, x);
+    if (!direct) {
+        const int64_t n4 = (int64_t)B * (D / 4);
+        hipLaunchKernelGGL(reduce_dx, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s, parts, p.splits,
+                           (int64_t)B * D, B, D, dX_partial, lddx, accumulate_dx);
+    }
+
+    DwArgs w;
+    w.X = a.X; w.ldx = ldx; w.dZ = dZ; w.ldz = p.Cpad;
+    w.B = B; w.D = D; w.C = C_shard;
+    w.nDT = p.nDT; w.nCT = p.nCT; w.k_steps = (B + TILE_K - 1) / TILE_K;
+    w.dW = static_cast<uint16_t*>(dW_shard); w.lddw = lddw;
+    hipLaunchKernelGGL(bwd_dw, dim3(xcd_grid(p.nDT * p.nCT)), dim3(NTHREADS), 0, s, w);
+    return launch_status();
+}
+
+}  // extern "C"

@@ -1,0 +1,149 @@
+"""Helpers for the GPU parity tests: run one training step of the split head through the
+C-ABI binding, run the fp64 oracle on the same bits, and compare to the stated tolerances.
+Not collected by pytest (no test_ prefix)."""
+import sys
+
+import numpy as np
+import torch
+
+from oracle import oracle
+from paper_2011_09208_amd import inputs
+
+# Tolerances of the parity gate (bf16 inputs, fp32 accumulation).
+LOSS_REL = 1e-3
+LSE_ABS = 2e-3
+GRAD_REL_TO_MAX = 2e-2
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def dev_bf16(bits: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def bf16_to_f64(t: torch.Tensor) -> np.ndarray:
+    return inputs.bf16_bits_to_f64(t.view(torch.int16).cpu().numpy().view(np.uint16))
+
+
+def run_step(X_bits, W_bits, bias, labels, shards, g=1.0, w_lo=0, want_db=True, loss_mean=False):
+    """fwd on every shard -> combine -> bwd on every shard (dX accumulated across shards).
+
+    W_bits holds classes [w_lo, w_lo + rows); `shards` = [(class_offset, C_shard)].
+    Returns numpy arrays: per-shard m, s, t [S, B]; lse, loss [B]; dX [B, D];
+    dW list of [C_s, D] (float64 upcast of bf16), db list of [C_s].
+    """
+    from paper_2011_09208_amd import binding as ws
+
+    X = dev_bf16(X_bits)
+    W = dev_bf16(W_bits)
+    B, D = X.shape
+    y = torch.from_numpy(np.ascontiguousarray(labels, dtype=np.int32)).cuda()
+    b_dev = None if bias is None else torch.from_numpy(np.ascontiguousarray(bias, dtype=np.float32)).cuda()
+    S = len(shards)
+    m = torch.full((S, B), float("nan"), device="cuda")
+    s = torch.full((S, B), float("nan"), device="cuda")
+    t = torch.full((S, B), float("nan"), device="cuda")
+    lse = torch.full((B,), float("nan"), device="cuda")
+    loss = torch.full((B,), float("nan"), device="cuda")
+    mean = torch.full((1,), float("nan"), device="cuda") if loss_mean else None
+    fwd_ws = max(ws.fwd_workspace_bytes(B, D, c) for _, c in shards)
+    bwd_ws = max(ws.bwd_workspace_bytes(B, D, c) for _, c in shards)
+    work = torch.empty(max(fwd_ws, bwd_ws), dtype=torch.uint8, device="cuda")
+    work.fill_(0xFF)       # NaN patterns: stale workspace must never leak into a result
+    for i, (off, c) in enumerate(shards):
+        Ws = W[off - w_lo: off - w_lo + c]
+        bs = None if b_dev is None else b_dev[off - w_lo: off - w_lo + c]
+        ws.split_fc_fwd(X, Ws, bs, y, off, m[i], s[i], t[i], work)
+    ws.combine_partials(m, s, t, lse, loss, mean)
+    dX = torch.full((B, D), float("nan"), device="cuda")
+    dWs, dbs = [], []
+    for i, (off, c) in enumerate(shards):
+        Ws = W[off - w_lo: off - w_lo + c]
+        bs = None if b_dev is None else b_dev[off - w_lo: off - w_lo + c]
+        dW = torch.full((c, D), float("nan"), device="cuda", dtype=torch.bfloat16)
+        db = torch.full((c,), float("nan"), device="cuda") if want_db else None
+        ws.split_fc_bwd(X, Ws, bs, lse, y, off, g, dX, i > 0, dW, db, work)
+        dWs.append(dW)
+        dbs.append(db)
+    torch.cuda.synchronize()
+    out = dict(m=m.cpu().numpy(), s=s.cpu().numpy(), t=t.cpu().numpy(), lse=lse.cpu().numpy(),
+               loss=loss.cpu().numpy(), dX=dX.cpu().numpy(),
+               dW=[bf16_to_f64(w) for w in dWs],
+               db=[None if d is None else d.cpu().numpy() for d in dbs])
+    if loss_mean:
+        out["loss_mean"] = float(mean.cpu().numpy()[0])
+    return out
+
+
+def oracle_step(X_bits, W_bits, bias, labels, shards, g=1.0, w_lo=0):
+    """The same step by the oracle: unsharded result over the union of the shards plus per-shard statistics.
+    The shards must tile a contiguous class range that starts at w_lo."""
+    X = inputs.bf16_bits_to_f64(X_bits)
+    W = inputs.bf16_bits_to_f64(W_bits)
+    b = None if bias is None else np.asarray(bias, dtype=np.float64)
+    y = np.asarray(labels, dtype=np.int64)
+    ms, ss, ts = [], [], []
+    for off, c in shards:
+        sl = slice(off - w_lo, off - w_lo + c)
+        mm, sss, tt = oracle.partials(X, W[sl], None if b is None else b[sl], y, off)
+        ms.append(mm), ss.append(sss), ts.append(tt)
+    lse, loss = oracle.combine(ms, ss, ts)
+    dX = np.zeros_like(X)
+    dWs, dbs = [], []
+    for off, c in shards:
+        sl = slice(off - w_lo, off - w_lo + c)
+        gr = oracle.shard_grads(X, W[sl], None if b is None else b[sl], lse, y, off, g)
+        dX += gr["dX_partial"]
+        dWs.append(gr["dW"])
+        dbs.append(gr["db"])
+    return dict(m=np.stack(ms), s=np.stack(ss), t=np.stack(ts), lse=lse, loss=loss, dX=dX, dW=dWs, db=dbs)
+
+
+def max_rel_to_max(got, ref):
+    scale = np.max(np.abs(ref))
+    if scale == 0.0:
+        return float(np.max(np.abs(got)))
+    return float(np.max(np.abs(got - ref)) / scale)
+
+
+def compare(got, ref, labels, shards, tag=""):
+    """Asserts the parity gate; returns a dict of the error figures."""
+    y = np.asarray(labels, dtype=np.int64)
+    rep = {}
+    for k in ("m", "s", "t", "lse", "loss", "dX"):
+        assert np.all(np.isfinite(got[k])), f"{tag}: non-finite values in {k}"
+    # integer part: label logit is exactly zero outside the shard and owned by exactly one shard
+    for i, (off, c) in enumerate(shards):
+        inside = (y >= off) & (y < off + c)
+        assert np.all(got["t"][i][~inside] == 0.0), f"{tag}: label_logit not exactly 0 outside shard {i}"
+    rep["row_max_abs"] = float(np.max(np.abs(got["m"] - ref["m"])))
+    rep["sumexp_rel"] = float(np.max(np.abs(got["s"] - ref["s"]) / ref["s"]))
+    rep["label_logit_abs"] = float(np.max(np.abs(got["t"] - ref["t"])))
+    rep["lse_abs"] = float(np.max(np.abs(got["lse"] - ref["lse"])))
+    rep["loss_rel"] = float(np.max(np.abs(got["loss"] - ref["loss"]) / np.maximum(np.abs(ref["loss"]), 1e-30)))
+    rep["loss_abs"] = float(np.max(np.abs(got["loss"] - ref["loss"])))
+    zscale = max(1.0, float(np.max(np.abs(ref["m"]))))
+    assert rep["row_max_abs"] <= LSE_ABS * zscale, (tag, rep)
+    assert rep["sumexp_rel"] <= 1e-3 + LSE_ABS * zscale, (tag, rep)
+    assert rep["label_logit_abs"] <= LSE_ABS * zscale, (tag, rep)
+    assert rep["lse_abs"] <= LSE_ABS * zscale, (tag, rep)
+    # loss can be ~0 for a dominant label logit: gate it relatively where it is not tiny
+    ok = np.abs(got["loss"] - ref["loss"]) <= LOSS_REL * np.abs(ref["loss"]) + LSE_ABS * zscale * 1e-1
+    assert np.all(ok), (tag, rep)
+    rep["dX"] = max_rel_to_max(got["dX"], ref["dX"])
+    assert rep["dX"] <= GRAD_REL_TO_MAX, (tag, rep)
+    rep["dW"], rep["db"] = 0.0, 0.0
+    wscale = max(np.max(np.abs(w)) for w in ref["dW"]) or 1.0     # a one-class layer has zero gradients
+    bscale = max(np.max(np.abs(d)) for d in ref["db"]) or 1.0
+    for i in range(len(shards)):
+        assert np.all(np.isfinite(got["dW"][i])), f"{tag}: non-finite dW in shard {i}"
+        rep["dW"] = max(rep["dW"], float(np.max(np.abs(got["dW"][i] - ref["dW"][i])) / wscale))
+        if got["db"][i] is not None:
+            assert np.all(np.isfinite(got["db"][i])), f"{tag}: non-finite db in shard {i}"
+            rep["db"] = max(rep["db"], float(np.max(np.abs(got["db"][i] - ref["db"][i])) / bscale))
+    assert rep["dW"] <= GRAD_REL_TO_MAX, (tag, rep)
+    assert rep["db"] <= GRAD_REL_TO_MAX, (tag, rep)
+    return rep

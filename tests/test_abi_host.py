@@ -1,0 +1,94 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, and rejects bad arguments before any HIP call."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def ws():
+    from paper_2011_09208_amd import buildlib
+    if buildlib.is_stale():
+        buildlib.build()
+    from paper_2011_09208_amd import binding
+    return binding
+
+
+def test_header_symbols_are_exported(ws):
+    text = open(os.path.join(ROOT, "include", "whalesplit.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(ws_[a-z_]+)\s*\(", text))
+    assert declared == set(ws.EXPORTS)
+    for name in declared:
+        assert getattr(ws.lib, name) is not None
+
+
+def test_version_and_status_strings(ws):
+    assert ws.version() >= 1000
+    names = [ws.status_string(i) for i in range(7)]
+    assert names == ["WS_OK", "WS_ERR_NULL", "WS_ERR_SHAPE", "WS_ERR_ALIGN", "WS_ERR_RANGE",
+                     "WS_ERR_WORKSPACE", "WS_ERR_HIP"]
+    assert ws.status_string(99) == "WS_ERR_UNKNOWN"
+
+
+def test_workspace_queries(ws):
+    assert ws.fwd_workspace_bytes(0, 64, 1) == 0 and ws.bwd_workspace_bytes(4, 65, 1) == 0
+    # one (max, sum) pair per 256-class tile and padded row
+    assert ws.fwd_workspace_bytes(1024, 2048, 100_000) == 2 * 391 * 1024 * 4
+    # dz in bf16 on whole tiles, plus the split-K partial sums of dX
+    b = ws.bwd_workspace_bytes(1024, 2048, 100_000)
+    assert b >= 1024 * 100_096 * 2 and (b - 1024 * 100_096 * 2) % (1024 * 2048 * 4) == 0
+    assert ws.bwd_workspace_bytes(32, 256, 500) >= 256 * 512 * 2
+
+
+A = 0x10000          # fake, 16-byte aligned "device" addresses: validation never dereferences them
+
+
+def _fwd(ws, X=A, ldx=64, W=A, ldw=64, b=None, y=A, B=4, D=64, C=8, off=0, m=A, s=A, t=A, wsp=A, wsb=1 << 20):
+    return ws.lib.ws_split_fc_fwd(X, ldx, W, ldw, b, y, B, D, C, off, m, s, t, wsp, wsb, None)
+
+
+def _bwd(ws, X=A, ldx=64, W=A, ldw=64, b=None, lse=A, y=A, B=4, D=64, C=8, off=0, g=1.0, dX=A, lddx=64,
+         acc=0, dW=A, lddw=64, db=None, wsp=A, wsb=1 << 24):
+    return ws.lib.ws_split_fc_bwd(X, ldx, W, ldw, b, lse, y, B, D, C, off, g, dX, lddx, acc, dW, lddw, db,
+                                  wsp, wsb, None)
+
+
+def test_fwd_validation(ws):
+    E = {n: i for i, n in enumerate(["OK", "NULL", "SHAPE", "ALIGN", "RANGE", "WORKSPACE", "HIP"])}
+    assert _fwd(ws, X=None) == E["NULL"] and _fwd(ws, W=None) == E["NULL"] and _fwd(ws, y=None) == E["NULL"]
+    assert _fwd(ws, m=None) == E["NULL"] and _fwd(ws, s=None) == E["NULL"] and _fwd(ws, t=None) == E["NULL"]
+    assert _fwd(ws, B=0) == E["SHAPE"] and _fwd(ws, C=-1) == E["SHAPE"] and _fwd(ws, D=72, ldx=72, ldw=72) == E["SHAPE"]
+    assert _fwd(ws, ldx=32) == E["SHAPE"] and _fwd(ws, ldw=56) == E["SHAPE"]
+    assert _fwd(ws, off=-1) == E["RANGE"] and _fwd(ws, off=2**31 - 4) == E["RANGE"]
+    assert _fwd(ws, X=A + 2) == E["ALIGN"] and _fwd(ws, W=A + 8) == E["ALIGN"] and _fwd(ws, ldx=68) == E["ALIGN"]
+    assert _fwd(ws, m=A + 2) == E["ALIGN"] and _fwd(ws, b=A + 1) == E["ALIGN"]
+    assert _fwd(ws, wsp=None) == E["WORKSPACE"] and _fwd(ws, wsb=16) == E["WORKSPACE"]
+    assert _fwd(ws, wsp=A + 4) == E["ALIGN"]
+
+
+def test_bwd_validation(ws):
+    E = {n: i for i, n in enumerate(["OK", "NULL", "SHAPE", "ALIGN", "RANGE", "WORKSPACE", "HIP"])}
+    assert _bwd(ws, lse=None) == E["NULL"] and _bwd(ws, dX=None) == E["NULL"] and _bwd(ws, dW=None) == E["NULL"]
+    assert _bwd(ws, X=None) == E["NULL"]
+    assert _bwd(ws, D=0) == E["SHAPE"] and _bwd(ws, lddx=60) == E["SHAPE"] and _bwd(ws, lddw=8) == E["SHAPE"]
+    assert _bwd(ws, off=-5) == E["RANGE"]
+    assert _bwd(ws, dX=A + 4) == E["ALIGN"] and _bwd(ws, dW=A + 2) == E["ALIGN"] and _bwd(ws, lddw=68) == E["ALIGN"]
+    assert _bwd(ws, db=A + 3) == E["ALIGN"] and _bwd(ws, lddx=66) == E["ALIGN"]
+    assert _bwd(ws, wsb=1024) == E["WORKSPACE"] and _bwd(ws, wsp=None) == E["WORKSPACE"]
+
+
+def test_combine_validation(ws):
+    f = ws.lib.ws_combine_partials
+    assert f(None, A, A, 1, 4, 4, A, A, None, None) == 1
+    assert f(A, A, A, 1, 4, 4, None, A, None, None) == 1
+    assert f(A, A, A, 1, 0, 4, A, A, None, None) == 2
+    assert f(A, A, A, 2, 8, 4, A, A, None, None) == 2
+    assert f(A, A, A, 0, 4, 4, A, A, None, None) == 4
+    assert f(A, A, A, 70000, 4, 4, A, A, None, None) == 4
+    assert f(A + 1, A, A, 1, 4, 4, A, A, None, None) == 3
+    assert f(A, A, A, 1, 4, 4, A, A, A + 2, None) == 3
