@@ -1,0 +1,187 @@
+#!/usr/bin/env python3
+"""Benchmark of the split fully-connected + softmax head on one MI355X.
+
+One step = the whole hot path over one synthetic batch: split_fc_fwd on every shard ->
+combine_partials -> split_fc_bwd on every shard, through the C-ABI library, inputs resident
+in HBM.  Workload: the paper's motivating classifier at the headline shape (B = 1024 rows,
+D = 2048 features, C = 100 000 classes as one shard; Section 1, Section 2.1).
+
+Prints ONE JSON line: samples/s for fwd+bwd, the MFMA roofline of the slowest GEMM kernel
+(algorithmic flops per launch / average launch time from HIP events recorded on the launch
+stream inside the timed region), the per-kernel breakdown, and the fp64 oracle timed on the
+host cores as a CPU baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+BF16_DENSE_PEAK_TFLOPS = 2516.6      # 256 CUs x 2.4 GHz x 4096 flop/clk/CU
+HBM_PEAK_GBS = 8000.0
+GEMM_KERNELS = ("fwd_logits_stats", "bwd_recompute_dz", "bwd_dx", "bwd_dw")
+
+
+def read_traffic(workload):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary, if any."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    if not os.path.exists(path):
+        return {}
+    out = {}
+    with open(path) as f:
+        for line in f:
+            parts = line.split()
+            if len(parts) >= 2 and parts[0].startswith("traffic_bytes:"):
+                out[parts[0].split(":", 1)[1]] = float(parts[1])
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="headline")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (one shard per call, shards run one after another); "
+                 "--gpus must be 1")
+
+    import numpy as np
+    import torch
+    from paper_2011_09208_amd import inputs
+    from paper_2011_09208_amd import binding as ws      # raises if the HIP library is not built
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; there is no CPU fallback")
+
+    # cfg5 times its first shard only (50 000 of 400 000 classes); the other rows of W are not kept
+    p = inputs.make_config(args.workload, w_rows=50_000 if args.workload == "cfg5" else None)
+    B, D = p.B, p.D
+    shards = p.shards if args.workload != "cfg5" else p.shards[:1]
+    C = p.W_bits.shape[0]
+    dev = torch.device("cuda:0")
+    X = torch.from_numpy(p.X_bits.view(np.int16)).to(dev).view(torch.bfloat16)
+    W = torch.from_numpy(p.W_bits.view(np.int16)).to(dev).view(torch.bfloat16)
+    y = torch.from_numpy(p.labels).to(dev)
+    S = len(shards)
+    m = torch.empty((S, B), device=dev)
+    s = torch.empty((S, B), device=dev)
+    t = torch.empty((S, B), device=dev)
+    lse = torch.empty(B, device=dev)
+    loss = torch.empty(B, device=dev)
+    dX = torch.empty((B, D), device=dev)
+    dW = torch.empty((W.shape[0], D), device=dev, dtype=torch.bfloat16)
+    db = torch.empty(W.shape[0], device=dev)
+    nbytes = max(max(ws.fwd_workspace_bytes(B, D, c), ws.bwd_workspace_bytes(B, D, c)) for _, c in shards)
+    work = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+
+    def step():
+        for i, (off, c) in enumerate(shards):
+            ws.split_fc_fwd(X, W[off:off + c], None, y, off, m[i], s[i], t[i], work)
+        ws.combine_partials(m, s, t, lse, loss, None)
+        for i, (off, c) in enumerate(shards):
+            ws.split_fc_bwd(X, W[off:off + c], None, lse, y, off, 1.0, dX, i > 0, dW[off:off + c],
+                            db[off:off + c], work)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # untimed-by-events run first: the wall-clock figure without any event records in the stream
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    plain_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # the timed region proper: every kernel launch bracketed by HIP events on its stream
+    ws.profile_enable(args.steps * (9 * S + 2) + 16)
+    ws.profile_reset()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    prof = ws.profile_read()
+    ws.profile_enable(0)
+
+    c_total = sum(c for _, c in shards)
+    kernels = {}
+    for name, (tot_ms, n) in prof.items():
+        avg = tot_ms / n
+        kernels[name] = {"avg_ms": round(avg, 5), "launches_per_step": n / args.steps}
+    # each GEMM kernel launch performs 2 * B * D * C_shard flops; with several shards take the mean launch
+    flops_per_launch = 2.0 * B * D * c_total / S
+    dominant = max(GEMM_KERNELS, key=lambda k: kernels[k]["avg_ms"])
+    for k in GEMM_KERNELS:
+        kernels[k]["tflops"] = round(flops_per_launch / (kernels[k]["avg_ms"] * 1e-3) / 1e12, 2)
+    achieved = kernels[dominant]["tflops"]
+    traffic = read_traffic(args.workload).get(dominant)
+    credited = 6.0 * B * D * c_total
+    value = B / (ms_per_step * 1e-3)
+
+    result = {
+        "metric": "split-FC fwd+bwd samples/sec at D=2048,C=100K,B=1024; % bf16 MFMA peak",
+        "value": round(value, 1),
+        "unit": "samples/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload}: B={B} D={D} C={C} shards={S} (fwd all shards -> combine -> bwd all shards)"},
+        "pct_bf16_mfma_peak_credited_6BDC": round(100.0 * credited / (ms_per_step * 1e-3) / (BF16_DENSE_PEAK_TFLOPS * 1e12), 2),
+        "pct_bf16_mfma_peak_executed_8BDC": round(100.0 * credited * 8 / 6 / (ms_per_step * 1e-3) / (BF16_DENSE_PEAK_TFLOPS * 1e12), 2),
+        "ms_per_step_without_event_records": round(plain_ms, 4),
+        "roofline": {
+            "bound": "mfma",
+            "kernel": dominant,
+            "achieved": achieved,
+            "peak": BF16_DENSE_PEAK_TFLOPS,
+            "unit": "TFLOP/s",
+            "frac": round(achieved / BF16_DENSE_PEAK_TFLOPS, 4),
+            "traffic": traffic,
+        },
+        "kernels": kernels,
+    }
+
+    if not args.no_cpu_baseline and args.workload != "cfg5":   # cfg5 keeps one shard of W only: no unsharded oracle
+        # The oracle as it stands, on the host cores, on one full step of the same workload
+        # (or a row sample of it when the step would take minutes).
+        from oracle import oracle
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([d.get("num_threads", 1) for d in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count()
+        rows = B if 6.0 * B * D * C <= 2.0e12 else max(1, int(2.0e12 / (6.0 * D * C)))
+        Xo = inputs.bf16_bits_to_f64(p.X_bits[:rows])
+        Wo = inputs.bf16_bits_to_f64(p.W_bits)
+        t0 = time.perf_counter()
+        ref = oracle.unsharded(Xo, Wo, None, p.labels[:rows], 1.0)
+        dt = time.perf_counter() - t0
+        result["cpu_baseline"] = {
+            "value": round(rows / dt, 2),
+            "unit": "samples/s",
+            "cores": int(cores),
+            "kind": "oracle",
+            "sample": f"one fwd+bwd step of the fp64 numpy oracle on {rows} of {B} rows, all {C} classes, {dt:.1f} s",
+        }
+        got = lse.cpu().numpy()[:rows]
+        result["cpu_baseline"]["max_abs_lse_diff_vs_gpu"] = float(np.max(np.abs(got - ref["lse"])))
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -128,6 +128,20 @@ int ws_split_fc_bwd(const void* X, int64_t ldx,
                     float* db_shard,
                     void* workspace, size_t workspace_bytes, void* stream);
 
+/* Optional per-kernel timing, for benchmarks (not part of the paper's method; host-side state,
+ * not thread safe).  ws_profile_enable(n) creates a pool of n event pairs (n <= 0 switches
+ * timing off and frees the pool); while the pool lasts, every kernel the library launches is
+ * bracketed by two events recorded on the launch stream.  ws_profile_reset() starts a new
+ * measurement.  ws_profile_read() waits for the recorded events of one kernel (indices
+ * 0 .. ws_profile_kernel_count() - 1, names from ws_profile_kernel_name) and returns the summed
+ * duration in milliseconds and the number of timed launches.  total_ms and launches are HOST
+ * pointers. */
+int ws_profile_enable(int32_t max_launches);
+int ws_profile_reset(void);
+int32_t ws_profile_kernel_count(void);
+const char* ws_profile_kernel_name(int32_t kernel);
+int ws_profile_read(int32_t kernel, double* total_ms, int64_t* launches);
+
 #ifdef __cplusplus
 }
 #endif

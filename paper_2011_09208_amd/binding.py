@@ -38,8 +38,21 @@ lib.ws_split_fc_bwd.restype = ctypes.c_int
 lib.ws_split_fc_bwd.argtypes = [_p, _i64, _p, _i64, _p, _p, _p, _i32, _i32, _i32, _i32, _f32,
                                 _p, _i64, _i32, _p, _i64, _p, _p, _sz, _p]
 
+lib.ws_profile_enable.restype = ctypes.c_int
+lib.ws_profile_enable.argtypes = [_i32]
+lib.ws_profile_reset.restype = ctypes.c_int
+lib.ws_profile_reset.argtypes = []
+lib.ws_profile_kernel_count.restype = _i32
+lib.ws_profile_kernel_count.argtypes = []
+lib.ws_profile_kernel_name.restype = ctypes.c_char_p
+lib.ws_profile_kernel_name.argtypes = [_i32]
+lib.ws_profile_read.restype = ctypes.c_int
+lib.ws_profile_read.argtypes = [_i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
+
 EXPORTS = ["ws_status_string", "ws_version", "ws_fwd_workspace_bytes", "ws_split_fc_fwd",
-           "ws_combine_partials", "ws_bwd_workspace_bytes", "ws_split_fc_bwd"]
+           "ws_combine_partials", "ws_bwd_workspace_bytes", "ws_split_fc_bwd",
+           "ws_profile_enable", "ws_profile_reset", "ws_profile_kernel_count", "ws_profile_kernel_name",
+           "ws_profile_read"]
 
 
 class WhaleSplitError(RuntimeError):
@@ -109,3 +122,22 @@ def split_fc_bwd(X, W_shard, b_shard, logsumexp, labels, class_offset, grad_scal
                                _ptr(dX_partial), dX_partial.stride(0), int(bool(accumulate_dx)),
                                _ptr(dW_shard), dW_shard.stride(0), _ptr(db_shard), _ptr(workspace),
                                workspace.numel() * workspace.element_size(), _stream()))
+
+
+def profile_enable(max_launches):
+    _check(lib.ws_profile_enable(int(max_launches)))
+
+
+def profile_reset():
+    _check(lib.ws_profile_reset())
+
+
+def profile_read():
+    """{kernel name: (total_ms, launches)} for every kernel that was timed since the last reset."""
+    out = {}
+    for k in range(lib.ws_profile_kernel_count()):
+        ms, n = ctypes.c_double(0.0), ctypes.c_int64(0)
+        _check(lib.ws_profile_read(k, ctypes.byref(ms), ctypes.byref(n)))
+        if n.value:
+            out[lib.ws_profile_kernel_name(k).decode()] = (ms.value, n.value)
+    return out

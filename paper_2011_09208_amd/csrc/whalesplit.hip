@@ -446,6 +446,44 @@ static int check_fc_common(const void* X, int64_t ldx, const void* W, int64_t ld
     return WS_OK;
 }
 
+
+// ---- optional per-kernel timing --------------------------------------------------------------------
+// When enabled, every kernel launch is bracketed by a pair of events recorded on the launch stream.
+// The pairs come from a pool created by ws_profile_enable; when the pool is used up, launches go
+// untimed.  Not thread safe; meant for benchmarks.
+enum KernelId { KID_FWD = 0, KID_MERGE, KID_COMBINE, KID_MEAN, KID_DZ, KID_DB, KID_DX, KID_DXRED, KID_DW, KID_COUNT };
+static const char* const kKernelNames[KID_COUNT] = {"fwd_logits_stats", "merge_class_tiles", "combine_partials",
+                                                    "mean_loss", "bwd_recompute_dz", "colsum_db", "bwd_dx",
+                                                    "reduce_dx", "bwd_dw"};
+struct ProfState {
+    bool on = false;
+    int capacity = 0, used = 0;
+    hipEvent_t* start = nullptr;
+    hipEvent_t* stop = nullptr;
+    int* kid = nullptr;
+};
+static ProfState g_prof;
+
+struct ScopedTimer {
+    int slot = -1;
+    hipStream_t s;
+    ScopedTimer(int kid, hipStream_t stream) : s(stream) {
+        if (g_prof.on && g_prof.used < g_prof.capacity) {
+            slot = g_prof.used++;
+            g_prof.kid[slot] = kid;
+            (void)hipEventRecord(g_prof.start[slot], s);
+        }
+    }
+    ~ScopedTimer() {
+        if (slot >= 0) (void)hipEventRecord(g_prof.stop[slot], s);
+    }
+};
+#define WS_LAUNCH(kid, kernel, grid, block, stream, ...)                         \
+    do {                                                                         \
+        ScopedTimer timer_(kid, stream);                                         \
+        hipLaunchKernelGGL(kernel, grid, block, 0, stream, __VA_ARGS__);         \
+    } while (0)
+
 static int launch_status() { return hipGetLastError() == hipSuccess ? WS_OK : WS_ERR_HIP; }
 
 }  // namespace ws
@@ -501,9 +539,9 @@ int ws_split_fc_fwd(const void* X, int64_t ldx, const void* W_shard, int64_t ldw
     float* part_max = static_cast<float*>(workspace);
     float* part_sum = part_max + (size_t)a.nCT * a.Bpad;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    hipLaunchKernelGGL(fwd_logits_stats, dim3(xcd_grid(a.nBT * a.nCT)), dim3(NTHREADS), 0, s, a, part_max,
+    WS_LAUNCH(KID_FWD, fwd_logits_stats, dim3(xcd_grid(a.nBT * a.nCT)), dim3(NTHREADS), s, a, part_max,
                        part_sum, label_logit);
-    hipLaunchKernelGGL(merge_class_tiles, dim3((B + 255) / 256), dim3(256), 0, s, part_max, part_sum, a.nCT,
+    WS_LAUNCH(KID_MERGE, merge_class_tiles, dim3((B + 255) / 256), dim3(256), s, part_max, part_sum, a.nCT,
                        a.Bpad, B, row_max, row_sumexp);
     return launch_status();
 }
@@ -518,9 +556,9 @@ int ws_combine_partials(const float* row_max, const float* row_sumexp, const flo
         !aligned(loss_rows, 4) || (loss_mean && !aligned(loss_mean, 4)))
         return WS_ERR_ALIGN;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    hipLaunchKernelGGL(combine_partials_kernel, dim3((B + 255) / 256), dim3(256), 0, s, row_max, row_sumexp,
+    WS_LAUNCH(KID_COMBINE, combine_partials_kernel, dim3((B + 255) / 256), dim3(256), s, row_max, row_sumexp,
                        label_logit, S, B, shard_stride, logsumexp, loss_rows);
-    if (loss_mean) hipLaunchKernelGGL(mean_loss_kernel, dim3(1), dim3(1024), 0, s, loss_rows, B, loss_mean);
+    if (loss_mean) WS_LAUNCH(KID_MEAN, mean_loss_kernel, dim3(1), dim3(1024), s, loss_rows, B, loss_mean);
     return launch_status();
 }
 
@@ -549,10 +587,10 @@ int ws_split_fc_bwd(const void* X, int64_t ldx, const void* W_shard, int64_t ldw
     a.bias = b_shard; a.labels = labels;
     a.B = B; a.D = D; a.C = C_shard; a.class_offset = class_offset;
     a.Bpad = (int)p.Bpad; a.nBT = p.nBT; a.nCT = p.nCT;
-    hipLaunchKernelGGL(bwd_recompute_dz, dim3(xcd_grid(p.nBT * p.nCT)), dim3(NTHREADS), 0, s, a, logsumexp,
+    WS_LAUNCH(KID_DZ, bwd_recompute_dz, dim3(xcd_grid(p.nBT * p.nCT)), dim3(NTHREADS), s, a, logsumexp,
                        grad_scale, dZ, p.Cpad);
     if (db_shard)
-        hipLaunchKernelGGL(colsum_db, dim3((unsigned)(p.Cpad / 128)), dim3(256), 0, s, dZ, p.Cpad, B, C_shard,
+        WS_LAUNCH(KID_DB, colsum_db, dim3((unsigned)(p.Cpad / 128)), dim3(256), s, dZ, p.Cpad, B, C_shard,
                            db_shard);
 
     DxArgs x;
@@ -564,10 +602,10 @@ int ws_split_fc_bwd(const void* X, int64_t ldx, const void* W_shard, int64_t ldw
     x.out = direct ? dX_partial : parts;
     x.ldo = direct ? lddx : D;
     x.split_stride = (int64_t)B * D;
-    hipLaunchKernelGGL(bwd_dx, dim3(xcd_grid(p.nDT * p.nBT * p.splits)), dim3(NTHREADS), 0, s, x);
+    WS_LAUNCH(KID_DX, bwd_dx, dim3(xcd_grid(p.nDT * p.nBT * p.splits)), dim3(NTHREADS), s, x);
     if (!direct) {
         const int64_t n4 = (int64_t)B * (D / 4);
-        hipLaunchKernelGGL(reduce_dx, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s, parts, p.splits,
+        WS_LAUNCH(KID_DXRED, reduce_dx, dim3((unsigned)((n4 + 255) / 256)), dim3(256), s, parts, p.splits,
                            (int64_t)B * D, B, D, dX_partial, lddx, accumulate_dx);
     }
 
@@ -576,8 +614,59 @@ int ws_split_fc_bwd(const void* X, int64_t ldx, const void* W_shard, int64_t ldw
     w.B = B; w.D = D; w.C = C_shard;
     w.nDT = p.nDT; w.nCT = p.nCT; w.k_steps = (B + TILE_K - 1) / TILE_K;
     w.dW = static_cast<uint16_t*>(dW_shard); w.lddw = lddw;
-    hipLaunchKernelGGL(bwd_dw, dim3(xcd_grid(p.nDT * p.nCT)), dim3(NTHREADS), 0, s, w);
+    WS_LAUNCH(KID_DW, bwd_dw, dim3(xcd_grid(p.nDT * p.nCT)), dim3(NTHREADS), s, w);
     return launch_status();
+}
+
+int ws_profile_enable(int32_t max_launches) {
+    if (g_prof.start) {
+        for (int i = 0; i < g_prof.capacity; ++i) {
+            (void)hipEventDestroy(g_prof.start[i]);
+            (void)hipEventDestroy(g_prof.stop[i]);
+        }
+        delete[] g_prof.start; delete[] g_prof.stop; delete[] g_prof.kid;
+        g_prof = ProfState();
+    }
+    if (max_launches <= 0) return WS_OK;
+    g_prof.start = new hipEvent_t[max_launches];
+    g_prof.stop = new hipEvent_t[max_launches];
+    g_prof.kid = new int[max_launches];
+    for (int i = 0; i < max_launches; ++i) {
+        if (hipEventCreate(&g_prof.start[i]) != hipSuccess || hipEventCreate(&g_prof.stop[i]) != hipSuccess)
+            return WS_ERR_HIP;
+        g_prof.capacity = i + 1;
+    }
+    g_prof.on = true;
+    return WS_OK;
+}
+
+int ws_profile_reset(void) {
+    g_prof.used = 0;
+    return WS_OK;
+}
+
+int32_t ws_profile_kernel_count(void) { return KID_COUNT; }
+
+const char* ws_profile_kernel_name(int32_t kernel) {
+    return (kernel >= 0 && kernel < KID_COUNT) ? kKernelNames[kernel] : "";
+}
+
+int ws_profile_read(int32_t kernel, double* total_ms, int64_t* launches) {
+    if (!total_ms || !launches) return WS_ERR_NULL;
+    if (kernel < 0 || kernel >= KID_COUNT) return WS_ERR_RANGE;
+    double tot = 0.0;
+    int64_t n = 0;
+    for (int i = 0; i < g_prof.used; ++i) {
+        if (g_prof.kid[i] != kernel) continue;
+        if (hipEventSynchronize(g_prof.stop[i]) != hipSuccess) return WS_ERR_HIP;
+        float ms = 0.0f;
+        if (hipEventElapsedTime(&ms, g_prof.start[i], g_prof.stop[i]) != hipSuccess) return WS_ERR_HIP;
+        tot += ms;
+        ++n;
+    }
+    *total_ms = tot;
+    *launches = n;
+    return WS_OK;
 }
 
 }  // extern "C"
