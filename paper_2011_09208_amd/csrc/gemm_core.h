@@ -143,9 +143,57 @@ struct FragAddr {
 
 // ---- main loop ---------------------------------------------------------------------------------
 
+// Scheduling hint for one "slot" of the software pipeline: N MFMAs with NR LDS reads, NW LDS
+// writes and NV global loads spread evenly between them (the instructions themselves are written
+// before the hint; the hint only fixes their interleaving).
+template <int I, int N, int NR, int NW, int NV>
+struct SlotSched {
+    static __device__ __forceinline__ void apply() {
+        constexpr int H = (N + 1) / 2 + 1;      // reads go with the first MFMAs so they land before the slot ends
+        constexpr int r = I < H ? (NR * (I + 1) + H - 1) / H - (NR * I + H - 1) / H : 0;
+        constexpr int w = (NW * (I + 1) + N - 1) / N - (NW * I + N - 1) / N;
+        constexpr int v = (NV * (I + 1) + N - 1) / N - (NV * I + N - 1) / N;
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                  // one MFMA
+        if constexpr (r > 0) __builtin_amdgcn_sched_group_barrier(0x100, r, 0);   // LDS reads
+        if constexpr (w > 0) __builtin_amdgcn_sched_group_barrier(0x200, w, 0);   // LDS writes
+        if constexpr (v > 0) __builtin_amdgcn_sched_group_barrier(0x020, v, 0);   // global loads
+        if constexpr (I + 1 < N) SlotSched<I + 1, N, NR, NW, NV>::apply();
+        else __builtin_amdgcn_sched_barrier(0);      // nothing moves across the end of a slot
+    }
+};
+
+// Slot that also writes LDS: the reads are issued with the first half of the MFMAs and the writes
+// with the second half (the compiler must keep every read of the tile buffer ahead of the writes).
+template <int I, int N, int NR, int NW>
+struct SlotSchedRW {
+    static __device__ __forceinline__ void apply() {
+        constexpr int H = N / 2;
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if constexpr (I < H) {
+            constexpr int r = (NR * (I + 1) + H - 1) / H - (NR * I + H - 1) / H;
+            if constexpr (r > 0) __builtin_amdgcn_sched_group_barrier(0x100, r, 0);
+        } else {
+            constexpr int J = I - H, G = N - H;
+            constexpr int w = (NW * (J + 1) + G - 1) / G - (NW * J + G - 1) / G;
+            if constexpr (w > 0) __builtin_amdgcn_sched_group_barrier(0x200, w, 0);
+        }
+        if constexpr (I + 1 < N) SlotSchedRW<I + 1, N, NR, NW>::apply();
+        else __builtin_amdgcn_sched_barrier(0);
+    }
+};
+
 // acc[mt][nt] += A(m0 .. m0+255, k) * B(n0 .. n0+255, k) for k in [k_begin, k_begin + 64 * k_steps).
 // For a KC operand o0 is its first row; for a KS operand its first column.
 // Ends with a workgroup barrier, so LDS may be reused by the caller right away.
+//
+// Software pipeline of one k-step (stage s of the LDS double buffer holds it; the staging
+// registers hold the next k-step's tile, loaded one slot before this k-step began):
+//   slot 0  MFMAs of k-substep 0 | LDS reads of the fragments of substep 1
+//   slot 1  MFMAs of substep 1   | fragments of substep 2
+//   slot 2  MFMAs of substep 2   | fragments of substep 3 | staging registers -> LDS stage s^1
+//   barrier
+//   slot 3  MFMAs of substep 3   | fragments of substep 0 of stage s^1 | global loads of the
+//                                  k-step after next into the staging registers
 template <int AKIND, int BKIND>
 __device__ __forceinline__ void gemm_mainloop(f32x16 (&acc)[MT][NT], const Operand& A, const Operand& Bop,
                                               int m0, int n0, int k_begin, int k_steps, char* lds) {
@@ -153,6 +201,8 @@ __device__ __forceinline__ void gemm_mainloop(f32x16 (&acc)[MT][NT], const Opera
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int wm = wave >> 2, wn = wave & 3;
+    constexpr int NDSR = MT * (AKIND == KC ? 1 : 2) + NT * (BKIND == KC ? 1 : 2);
+    constexpr int NMFMA = MT * NT;
 
     FragAddr<AKIND, MT> fa;
     FragAddr<BKIND, NT> fb;
@@ -160,41 +210,78 @@ __device__ __forceinline__ void gemm_mainloop(f32x16 (&acc)[MT][NT], const Opera
     fb.init(lane, wn * WAVE_N);
 
     u32x4 sa[4], sb[4];
+    bf16x8 af[2][MT], bfr[2][NT];
+
+    auto load_frags = [&](int set, const char* la, int ks) {
+#pragma unroll
+        for (int t = 0; t < MT; ++t) af[set][t] = fa.load(la, t, ks);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) bfr[set][t] = fb.load(la + OPERAND_TILE_BYTES, t, ks);
+    };
+    auto mfmas = [&](int set) {
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int j = 0; j < NT; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[set][i], bfr[set][j], acc[i][j], 0, 0, 0);
+    };
+
     tile_g2r<AKIND>(sa, A, m0, k_begin, tid);
     tile_g2r<BKIND>(sb, Bop, n0, k_begin, tid);
     tile_r2s<AKIND>(lds, sa, tid);
     tile_r2s<BKIND>(lds + OPERAND_TILE_BYTES, sb, tid);
-    __syncthreads();
-
-    for (int kt = 0; kt < k_steps; ++kt) {
-        const bool more = kt + 1 < k_steps;
-        if (more) {
-            const int k0 = k_begin + (kt + 1) * TILE_K;
-            tile_g2r<AKIND>(sa, A, m0, k0, tid);
-            tile_g2r<BKIND>(sb, Bop, n0, k0, tid);
-        }
-        const char* la = lds + (kt & 1) * STAGE_BYTES;
-        const char* lb = la + OPERAND_TILE_BYTES;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            bf16x8 af[MT], bfr[NT];
-#pragma unroll
-            for (int t = 0; t < MT; ++t) af[t] = fa.load(la, t, ks);
-#pragma unroll
-            for (int t = 0; t < NT; ++t) bfr[t] = fb.load(lb, t, ks);
-#pragma unroll
-            for (int i = 0; i < MT; ++i)
-#pragma unroll
-                for (int j = 0; j < NT; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-        }
-        if (more) {
-            char* ls = lds + ((kt + 1) & 1) * STAGE_BYTES;
-            tile_r2s<AKIND>(ls, sa, tid);
-            tile_r2s<BKIND>(ls + OPERAND_TILE_BYTES, sb, tid);
-        }
-        __syncthreads();
+    {
+        const int k1 = k_begin + (k_steps > 1 ? TILE_K : 0);
+        tile_g2r<AKIND>(sa, A, m0, k1, tid);
+        tile_g2r<BKIND>(sb, Bop, n0, k1, tid);
     }
+    __syncthreads();
+    load_frags(0, lds, 0);
+
+    const int last = k_steps - 1;
+    for (int kt = 0; kt < last; ++kt) {
+        const char* la = lds + (kt & 1) * STAGE_BYTES;
+        char* ln = lds + ((kt + 1) & 1) * STAGE_BYTES;
+        // slot 0
+        load_frags(1, la, 1);
+        mfmas(0);
+        SlotSched<0, NMFMA, NDSR, 0, 0>::apply();
+        // slot 1
+        load_frags(0, la, 2);
+        mfmas(1);
+        SlotSched<0, NMFMA, NDSR, 0, 0>::apply();
+        // slot 2
+        load_frags(1, la, 3);
+        mfmas(0);
+        tile_r2s<AKIND>(ln, sa, tid);
+        tile_r2s<BKIND>(ln + OPERAND_TILE_BYTES, sb, tid);
+        SlotSchedRW<0, NMFMA, NDSR, 8>::apply();
+        __syncthreads();
+        // slot 3 (the k-step after next is clamped to the last one: a harmless reload at the end)
+        load_frags(0, ln, 0);
+        mfmas(1);
+        {
+            const int kn = kt + 2 < k_steps ? kt + 2 : last;
+            const int k2 = k_begin + kn * TILE_K;
+            tile_g2r<AKIND>(sa, A, m0, k2, tid);
+            tile_g2r<BKIND>(sb, Bop, n0, k2, tid);
+        }
+        SlotSched<0, NMFMA, NDSR, 0, 8>::apply();
+    }
+    {   // last k-step: nothing left to stage
+        const char* la = lds + (last & 1) * STAGE_BYTES;
+        load_frags(1, la, 1);
+        mfmas(0);
+        SlotSched<0, NMFMA, NDSR, 0, 0>::apply();
+        load_frags(0, la, 2);
+        mfmas(1);
+        SlotSched<0, NMFMA, NDSR, 0, 0>::apply();
+        load_frags(1, la, 3);
+        mfmas(0);
+        SlotSched<0, NMFMA, NDSR, 0, 0>::apply();
+        mfmas(1);
+    }
+    __syncthreads();
 }
 
 __device__ __forceinline__ void zero_acc(f32x16 (&acc)[MT][NT]) {

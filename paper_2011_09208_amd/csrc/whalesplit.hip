@@ -161,20 +161,26 @@ __global__ __launch_bounds__(NTHREADS) void fwd_logits_stats(FcArgs a, float* __
     }
 }
 
-__global__ void merge_class_tiles(const float* __restrict__ part_max, const float* __restrict__ part_sum,
-                                  int nCT, int Bpad, int B, float* __restrict__ row_max,
-                                  float* __restrict__ row_sumexp) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= B) return;
-    float m = NEG_INF;
-    for (int t = 0; t < nCT; ++t) m = fmaxf(m, part_max[(int64_t)t * Bpad + i]);
-    float s = 0.0f;
-    for (int t = 0; t < nCT; ++t) {
-        const float mt = part_max[(int64_t)t * Bpad + i];
-        if (mt != NEG_INF) s += part_sum[(int64_t)t * Bpad + i] * __expf(mt - m);
+// One workgroup merges the class-tile partials of 64 rows: thread (r, q) folds tiles q, q + 16, ...
+// of row r online, then the 16 partial pairs of a row are merged through LDS in a fixed order.
+__global__ __launch_bounds__(1024) void merge_class_tiles(const float* __restrict__ part_max,
+                                                           const float* __restrict__ part_sum, int nCT, int Bpad,
+                                                           int B, float* __restrict__ row_max,
+                                                           float* __restrict__ row_sumexp) {
+    __shared__ float sm[16][64], ss[16][64];
+    const int r = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const int i = blockIdx.x * 64 + r;          // < Bpad: the partial arrays are padded to whole tiles
+    float m = NEG_INF, s = 0.0f;
+    for (int t = q; t < nCT; t += 16) merge_ms(m, s, part_max[(int64_t)t * Bpad + i], part_sum[(int64_t)t * Bpad + i]);
+    sm[q][r] = m;
+    ss[q][r] = s;
+    __syncthreads();
+    if (q == 0 && i < B) {
+#pragma unroll
+        for (int k = 1; k < 16; ++k) merge_ms(m, s, sm[k][r], ss[k][r]);
+        row_max[i] = m;
+        row_sumexp[i] = s;
     }
-    row_max[i] = m;
-    row_sumexp[i] = s;
 }
 
 __global__ void combine_partials_kernel(const float* __restrict__ row_max, const float* __restrict__ row_sumexp,
@@ -541,7 +547,7 @@ int ws_split_fc_fwd(const void* X, int64_t ldx, const void* W_shard, int64_t ldw
     hipStream_t s = static_cast<hipStream_t>(stream);
     WS_LAUNCH(KID_FWD, fwd_logits_stats, dim3(xcd_grid(a.nBT * a.nCT)), dim3(NTHREADS), s, a, part_max,
                        part_sum, label_logit);
-    WS_LAUNCH(KID_MERGE, merge_class_tiles, dim3((B + 255) / 256), dim3(256), s, part_max, part_sum, a.nCT,
+    WS_LAUNCH(KID_MERGE, merge_class_tiles, dim3((B + 63) / 64), dim3(1024), s, part_max, part_sum, a.nCT,
                        a.Bpad, B, row_max, row_sumexp);
     return launch_status();
 }
