@@ -61,43 +61,40 @@ struct Operand {
 };
 
 // ---- global -> registers -> LDS staging ---------------------------------------------------
+// A 32 KiB operand tile is 2048 chunks of 16 bytes; thread t moves chunks t, t + 512, t + 1024 and
+// t + 1536.  Chunk set j (one chunk per thread) is "quarter j" of the tile: rows 64 j .. 64 j + 63 of
+// a KC tile, k-rows 16 j .. 16 j + 15 of a KS tile.
 
 template <int KIND>
-__device__ __forceinline__ void tile_g2r(u32x4 (&st)[4], const Operand& op, int o0, int k0, int tid) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int q = tid + NTHREADS * j;
-        if (KIND == KC) {
-            const int row = q >> 3, ch = q & 7;
-            int r = o0 + row;
-            r = r < op.lim0 ? r : op.lim0;
-            st[j] = *reinterpret_cast<const u32x4*>(op.base + (int64_t)r * op.ld + k0 + ch * 8);
-        } else {
-            const int kr = q >> 5, ch = q & 31;
-            int k = k0 + kr;
-            k = k < op.lim0 ? k : op.lim0;
-            int c = o0 + ch * 8;
-            c = c < op.lim1 ? c : op.lim1;
-            st[j] = *reinterpret_cast<const u32x4*>(op.base + (int64_t)k * op.ld + c);
-        }
+__device__ __forceinline__ u32x4 quarter_g2r(const Operand& op, int o0, int k0, int tid, int j) {
+    const int q = tid + NTHREADS * j;
+    if (KIND == KC) {
+        const int row = q >> 3, ch = q & 7;
+        int r = o0 + row;
+        r = r < op.lim0 ? r : op.lim0;
+        return *reinterpret_cast<const u32x4*>(op.base + (int64_t)r * op.ld + k0 + ch * 8);
+    } else {
+        const int kr = q >> 5, ch = q & 31;
+        int k = k0 + kr;
+        k = k < op.lim0 ? k : op.lim0;
+        int c = o0 + ch * 8;
+        c = c < op.lim1 ? c : op.lim1;
+        return *reinterpret_cast<const u32x4*>(op.base + (int64_t)k * op.ld + c);
     }
 }
 
 template <int KIND>
-__device__ __forceinline__ void tile_r2s(char* lds, const u32x4 (&st)[4], int tid) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int q = tid + NTHREADS * j;
-        int off;
-        if (KIND == KC) {
-            const int row = q >> 3, ch = q & 7;
-            off = row * 128 + ((ch ^ ((row >> 1) & 7)) << 4);
-        } else {
-            const int kr = q >> 5, ch = q & 31;
-            off = kr * 512 + ((ch ^ ((kr & 3) << 2)) << 4);
-        }
-        *reinterpret_cast<u32x4*>(lds + off) = st[j];
+__device__ __forceinline__ void quarter_r2s(char* lds, const u32x4& v, int tid, int j) {
+    const int q = tid + NTHREADS * j;
+    int off;
+    if (KIND == KC) {
+        const int row = q >> 3, ch = q & 7;
+        off = row * 128 + ((ch ^ ((row >> 1) & 7)) << 4);
+    } else {
+        const int kr = q >> 5, ch = q & 31;
+        off = kr * 512 + ((ch ^ ((kr & 3) << 2)) << 4);
     }
+    *reinterpret_cast<u32x4*>(lds + off) = v;
 }
 
 // ---- LDS -> MFMA fragments ------------------------------------------------------------------
@@ -143,17 +140,18 @@ struct FragAddr {
 
 // ---- main loop ---------------------------------------------------------------------------------
 
-// Scheduling hint for one "slot" of the software pipeline: N MFMAs with NR LDS reads, NW LDS
-// writes and NV global loads spread evenly between them (the instructions themselves are written
-// before the hint; the hint only fixes their interleaving).
+// Scheduling hint for one slot of the software pipeline: N MFMAs; NR LDS reads go with the first
+// MFMAs (so that they land before the slot ends), then NW LDS writes, then NV global loads with the
+// last MFMAs.  The instructions are written before the hint; the hint only fixes their interleaving
+// (LDS reads stay ahead of LDS writes, as the compiler must assume they may alias).
 template <int I, int N, int NR, int NW, int NV>
 struct SlotSched {
     static __device__ __forceinline__ void apply() {
-        constexpr int H = (N + 1) / 2 + 1;      // reads go with the first MFMAs so they land before the slot ends
+        constexpr int H = (N + 1) / 2 + 1;
         constexpr int r = I < H ? (NR * (I + 1) + H - 1) / H - (NR * I + H - 1) / H : 0;
-        constexpr int w = (NW * (I + 1) + N - 1) / N - (NW * I + N - 1) / N;
-        constexpr int v = (NV * (I + 1) + N - 1) / N - (NV * I + N - 1) / N;
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                  // one MFMA
+        constexpr int w = (I >= N - 1 - NW && I < N - 1) ? 1 : 0;
+        constexpr int v = (I >= N - NV) ? 1 : 0;
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                        // one MFMA
         if constexpr (r > 0) __builtin_amdgcn_sched_group_barrier(0x100, r, 0);   // LDS reads
         if constexpr (w > 0) __builtin_amdgcn_sched_group_barrier(0x200, w, 0);   // LDS writes
         if constexpr (v > 0) __builtin_amdgcn_sched_group_barrier(0x020, v, 0);   // global loads
@@ -162,38 +160,21 @@ struct SlotSched {
     }
 };
 
-// Slot that also writes LDS: the reads are issued with the first half of the MFMAs and the writes
-// with the second half (the compiler must keep every read of the tile buffer ahead of the writes).
-template <int I, int N, int NR, int NW>
-struct SlotSchedRW {
-    static __device__ __forceinline__ void apply() {
-        constexpr int H = N / 2;
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        if constexpr (I < H) {
-            constexpr int r = (NR * (I + 1) + H - 1) / H - (NR * I + H - 1) / H;
-            if constexpr (r > 0) __builtin_amdgcn_sched_group_barrier(0x100, r, 0);
-        } else {
-            constexpr int J = I - H, G = N - H;
-            constexpr int w = (NW * (J + 1) + G - 1) / G - (NW * J + G - 1) / G;
-            if constexpr (w > 0) __builtin_amdgcn_sched_group_barrier(0x200, w, 0);
-        }
-        if constexpr (I + 1 < N) SlotSchedRW<I + 1, N, NR, NW>::apply();
-        else __builtin_amdgcn_sched_barrier(0);
-    }
-};
-
 // acc[mt][nt] += A(m0 .. m0+255, k) * B(n0 .. n0+255, k) for k in [k_begin, k_begin + 64 * k_steps).
 // For a KC operand o0 is its first row; for a KS operand its first column.
 // Ends with a workgroup barrier, so LDS may be reused by the caller right away.
 //
-// Software pipeline of one k-step (stage s of the LDS double buffer holds it; the staging
-// registers hold the next k-step's tile, loaded one slot before this k-step began):
-//   slot 0  MFMAs of k-substep 0 | LDS reads of the fragments of substep 1
-//   slot 1  MFMAs of substep 1   | fragments of substep 2
-//   slot 2  MFMAs of substep 2   | fragments of substep 3 | staging registers -> LDS stage s^1
-//   barrier
-//   slot 3  MFMAs of substep 3   | fragments of substep 0 of stage s^1 | global loads of the
-//                                  k-step after next into the staging registers
+// Software pipeline.  LDS holds two stages (k-step j in stage j & 1).  Iteration j multiplies
+// k-step j in four slots of 8 MFMAs each (one per 16-wide k-substep); the fragments of a substep
+// are read from LDS one slot ahead.  The tiles are staged through registers one quarter at a time,
+// so that LDS writes and global loads are spread evenly over the iteration and every global load
+// has a full iteration to land:
+//   slot x = 0, 1, 2:  quarter x of k-step j + 1: registers -> stage (j + 1) & 1; then the same
+//                      registers <- quarter x of k-step j + 2 from global memory
+//   barrier            (every wave has finished reading stage j & 1 and writing stage (j + 1) & 1)
+//   slot 3:            quarter 3 of k-step j + 2: registers -> stage j & 1 (free now); then the
+//                      registers <- quarter 3 of k-step j + 3
+// k-steps beyond the last are clamped to the last one (a harmless reload).
 template <int AKIND, int BKIND>
 __device__ __forceinline__ void gemm_mainloop(f32x16 (&acc)[MT][NT], const Operand& A, const Operand& Bop,
                                               int m0, int n0, int k_begin, int k_steps, char* lds) {
@@ -203,6 +184,7 @@ __device__ __forceinline__ void gemm_mainloop(f32x16 (&acc)[MT][NT], const Opera
     const int wm = wave >> 2, wn = wave & 3;
     constexpr int NDSR = MT * (AKIND == KC ? 1 : 2) + NT * (BKIND == KC ? 1 : 2);
     constexpr int NMFMA = MT * NT;
+    const int last = k_steps - 1;
 
     FragAddr<AKIND, MT> fa;
     FragAddr<BKIND, NT> fb;
@@ -225,58 +207,67 @@ __device__ __forceinline__ void gemm_mainloop(f32x16 (&acc)[MT][NT], const Opera
             for (int j = 0; j < NT; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[set][i], bfr[set][j], acc[i][j], 0, 0, 0);
     };
+    auto kofs = [&](int step) { return k_begin + (step < last ? step : last) * TILE_K; };
+    auto g2r = [&](int quarter, int step) {
+        sa[quarter] = quarter_g2r<AKIND>(A, m0, kofs(step), tid, quarter);
+        sb[quarter] = quarter_g2r<BKIND>(Bop, n0, kofs(step), tid, quarter);
+    };
+    auto r2s = [&](int quarter, char* stage) {
+        quarter_r2s<AKIND>(stage, sa[quarter], tid, quarter);
+        quarter_r2s<BKIND>(stage + OPERAND_TILE_BYTES, sb[quarter], tid, quarter);
+    };
 
-    tile_g2r<AKIND>(sa, A, m0, k_begin, tid);
-    tile_g2r<BKIND>(sb, Bop, n0, k_begin, tid);
-    tile_r2s<AKIND>(lds, sa, tid);
-    tile_r2s<BKIND>(lds + OPERAND_TILE_BYTES, sb, tid);
-    {
-        const int k1 = k_begin + (k_steps > 1 ? TILE_K : 0);
-        tile_g2r<AKIND>(sa, A, m0, k1, tid);
-        tile_g2r<BKIND>(sb, Bop, n0, k1, tid);
-    }
+    // prologue: stage 0 <- k-step 0; quarter 3 of k-step 1 -> stage 1; registers <- what the loop expects
+#pragma unroll
+    for (int q = 0; q < 4; ++q) g2r(q, 0);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) r2s(q, lds);
+    g2r(3, 1);
+    r2s(3, lds + STAGE_BYTES);
+#pragma unroll
+    for (int q = 0; q < 3; ++q) g2r(q, 1);
+    g2r(3, 2);
     __syncthreads();
     load_frags(0, lds, 0);
 
-    const int last = k_steps - 1;
-    for (int kt = 0; kt < last; ++kt) {
-        const char* la = lds + (kt & 1) * STAGE_BYTES;
-        char* ln = lds + ((kt + 1) & 1) * STAGE_BYTES;
+    for (int j = 0; j < last; ++j) {
+        char* lc = lds + (j & 1) * STAGE_BYTES;          // stage of k-step j
+        char* ln = lds + ((j + 1) & 1) * STAGE_BYTES;    // stage of k-step j + 1
         // slot 0
-        load_frags(1, la, 1);
+        load_frags(1, lc, 1);
         mfmas(0);
-        SlotSched<0, NMFMA, NDSR, 0, 0>::apply();
+        r2s(0, ln);
+        g2r(0, j + 2);
+        SlotSched<0, NMFMA, NDSR, 2, 2>::apply();
         // slot 1
-        load_frags(0, la, 2);
+        load_frags(0, lc, 2);
         mfmas(1);
-        SlotSched<0, NMFMA, NDSR, 0, 0>::apply();
+        r2s(1, ln);
+        g2r(1, j + 2);
+        SlotSched<0, NMFMA, NDSR, 2, 2>::apply();
         // slot 2
-        load_frags(1, la, 3);
+        load_frags(1, lc, 3);
         mfmas(0);
-        tile_r2s<AKIND>(ln, sa, tid);
-        tile_r2s<BKIND>(ln + OPERAND_TILE_BYTES, sb, tid);
-        SlotSchedRW<0, NMFMA, NDSR, 8>::apply();
+        r2s(2, ln);
+        g2r(2, j + 2);
+        SlotSched<0, NMFMA, NDSR, 2, 2>::apply();
         __syncthreads();
-        // slot 3 (the k-step after next is clamped to the last one: a harmless reload at the end)
+        // slot 3
         load_frags(0, ln, 0);
         mfmas(1);
-        {
-            const int kn = kt + 2 < k_steps ? kt + 2 : last;
-            const int k2 = k_begin + kn * TILE_K;
-            tile_g2r<AKIND>(sa, A, m0, k2, tid);
-            tile_g2r<BKIND>(sb, Bop, n0, k2, tid);
-        }
-        SlotSched<0, NMFMA, NDSR, 0, 8>::apply();
+        r2s(3, lc);
+        g2r(3, j + 3);
+        SlotSched<0, NMFMA, NDSR, 2, 2>::apply();
     }
     {   // last k-step: nothing left to stage
-        const char* la = lds + (last & 1) * STAGE_BYTES;
-        load_frags(1, la, 1);
+        const char* lc = lds + (last & 1) * STAGE_BYTES;
+        load_frags(1, lc, 1);
         mfmas(0);
         SlotSched<0, NMFMA, NDSR, 0, 0>::apply();
-        load_frags(0, la, 2);
+        load_frags(0, lc, 2);
         mfmas(1);
         SlotSched<0, NMFMA, NDSR, 0, 0>::apply();
-        load_frags(1, la, 3);
+        load_frags(1, lc, 3);
         mfmas(0);
         SlotSched<0, NMFMA, NDSR, 0, 0>::apply();
         mfmas(1);
