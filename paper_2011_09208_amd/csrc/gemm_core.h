@@ -302,4 +302,84 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
     return __builtin_bit_cast(uint32_t, r);
 }
 
+// ---- output tiles through LDS ------------------------------------------------------------------------
+// The MFMA accumulator layout gives a lane one N index and groups of four consecutive M indices, which
+// makes direct global stores 8 or 16 bytes wide and scattered over 32 rows.  Instead the 256 x 256 tile
+// is rounded to bf16 and laid out in LDS as [n][m] (512 bytes per n, sixteen-byte chunks XOR-swizzled
+// by n & 31; it fills the 128 KiB the main loop no longer needs), then written out row by row.
+
+// Byte offset of element (n, m) in the swizzled tile; m must be a multiple of 4 for 8-byte accesses.
+__device__ __forceinline__ int out_tile_offset(int n, int m) {
+    return n * 512 + ((((m >> 3) ^ n) & 31) << 4) + ((m & 7) << 1);
+}
+
+__device__ __forceinline__ void acc_to_lds_bf16(const f32x16 (&acc)[MT][NT], char* lds) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 2, wn = wave & 3, h = lane >> 5, jl = lane & 31;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int n = wn * WAVE_N + 32 * nt + jl;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int v4 = 0; v4 < 4; ++v4) {
+                u32x2 p;
+                p[0] = pack_bf16(acc[mt][nt][4 * v4 + 0], acc[mt][nt][4 * v4 + 1]);
+                p[1] = pack_bf16(acc[mt][nt][4 * v4 + 2], acc[mt][nt][4 * v4 + 3]);
+                *reinterpret_cast<u32x2*>(lds + out_tile_offset(n, wm * WAVE_M + 32 * mt + 8 * v4 + 4 * h)) = p;
+            }
+    }
+}
+
+// Writes the LDS tile to out[n][m] (row pitch ld elements, `out` = address of element (0, 0) of the
+// tile), rows n < n_valid and columns m < m_valid only (m_valid a multiple of 8).  A wave stores two
+// whole 512-byte rows per instruction.
+__device__ __forceinline__ void lds_tile_store_rows(const char* lds, uint16_t* out, int64_t ld, int n_valid,
+                                                    int m_valid) {
+    const int tid = threadIdx.x;
+#pragma unroll 4
+    for (int i = 0; i < 16; ++i) {
+        const int q = tid + NTHREADS * i;
+        const int n = q >> 5, cq = q & 31;
+        if (n < n_valid && cq * 8 < m_valid) {
+            const u32x4 v = *reinterpret_cast<const u32x4*>(lds + n * 512 + (((cq ^ n) & 31) << 4));
+            *reinterpret_cast<u32x4*>(out + (int64_t)n * ld + cq * 8) = v;
+        }
+    }
+}
+
+// Writes the LDS tile transposed, out[m][n] (`out` = address of element (m = 0, n = 0)), all 256 x 256
+// elements (the destination is padded to whole tiles), and returns in lanes 0..15 of each wave the
+// sums over all 256 n of columns m = 32 * wave + 16 * u + lane, u = 0, 1 (as rounded to bf16).
+// The transpose uses ds_read_b64_tr_b16: a block of 16 lanes reads 4 n-rows x 16 m-columns and
+// each lane receives the 4 n of one m.
+__device__ __forceinline__ void lds_tile_store_transposed(const char* lds, uint16_t* out, int64_t ld,
+                                                          float (&colsum)[2]) {
+    typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int blk = lane >> 4, i = lane & 15;
+    const int e = i >> 2;               // which of the four n-rows this lane addresses
+    const int mc = 4 * (i & 3);         // first of the four m-columns this lane addresses
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int m0 = 32 * wave + 16 * u;
+        float sum = 0.0f;
+#pragma unroll 2
+        for (int it = 0; it < 8; ++it) {
+            const int n0 = 32 * it + 8 * blk;            // this block of lanes covers n0 .. n0 + 7
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (lds_s16x4_ptr)(lds + out_tile_offset(n0 + e, m0 + mc)));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (lds_s16x4_ptr)(lds + out_tile_offset(n0 + 4 + e, m0 + mc)));
+            const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) sum += __uint_as_float(((uint32_t)(uint16_t)v[k]) << 16);
+            *reinterpret_cast<s16x8*>(out + (int64_t)(m0 + i) * ld + n0) = v;
+        }
+        sum += __shfl_xor(sum, 16, 64);
+        sum += __shfl_xor(sum, 32, 64);
+        colsum[u] = sum;
+    }
+}
+
 }  // namespace ws

@@ -5,10 +5,12 @@
 //                      logit reduced in the epilogue; one (max, sum) partial per 256-class tile
 //   merge_class_tiles  merges those partials into row_max / row_sumexp of the shard
 //   combine_partials   merges the shards' statistics into logsumexp and loss
-//   bwd_recompute_dz   same GEMM again, epilogue dz = g (exp(z - lse) - onehot) stored as bf16
-//   colsum_db          db = column sums of dz
+//   bwd_recompute_dz   same GEMM again, epilogue dz = g (exp(z - lse) - onehot) stored as bf16,
+//                      both row-major and transposed
+//   finish_db          db = sum over the row tiles of the column sums bwd_recompute_dz produced
 //   bwd_dx             dX_partial = dz . W_s, split along the class contraction; partial sums
 //   reduce_dx          sums the split-K partials (optionally accumulating into the caller's dX)
+//   transpose_x        X^T for the dW contraction
 //   bwd_dw             dW_s = dz^T . X
 #include <hip/hip_runtime.h>
 #include <limits.h>
@@ -218,7 +220,8 @@ __global__ __launch_bounds__(1024) void mean_loss_kernel(const float* __restrict
 
 __global__ __launch_bounds__(NTHREADS) void bwd_recompute_dz(FcArgs a, const float* __restrict__ logsumexp,
                                                               float grad_scale, uint16_t* __restrict__ dZ,
-                                                              int64_t ldz) {
+                                                              int64_t ldz, uint16_t* __restrict__ dZT,
+                                                              int64_t ldzt, float* __restrict__ db_part) {
     __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
     const int tile = xcd_logical_tile(a.nBT * a.nCT);
     if (tile < 0) return;
@@ -254,44 +257,44 @@ __global__ __launch_bounds__(NTHREADS) void bwd_recompute_dz(FcArgs a, const flo
                 for (int v = 0; v < 16; ++v)
                     if (mine && acc_row(mt, v, h) == rel) acc[mt][nt][v] -= g;
         }
-        uint16_t* zrow = dZ + (int64_t)row * ldz + cw0 + 4 * h;
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-            for (int v4 = 0; v4 < 4; ++v4) {
-                u32x2 p;
-                p[0] = pack_bf16(acc[mt][nt][4 * v4 + 0], acc[mt][nt][4 * v4 + 1]);
-                p[1] = pack_bf16(acc[mt][nt][4 * v4 + 2], acc[mt][nt][4 * v4 + 3]);
-                *reinterpret_cast<u32x2*>(zrow + 32 * mt + 8 * v4) = p;
-            }
+    }
+
+    // dz goes out twice: [row][class] feeds the dX contraction (over classes) and [class][row] the dW
+    // contraction (over rows), so both read it contiguous along their contraction index.  The tile is
+    // staged in LDS so that both copies leave in whole rows; the transposed pass also yields the
+    // tile's column sums, this row tile's share of db.
+    __syncthreads();                       // the bias staging area is about to be overwritten
+    acc_to_lds_bf16(acc, lds);
+    __syncthreads();
+    lds_tile_store_rows(lds, dZ + (int64_t)bt * TILE_N * ldz + ct * TILE_M, ldz, TILE_N, TILE_M);
+    float colsum[2];
+    lds_tile_store_transposed(lds, dZT + (int64_t)ct * TILE_M * ldzt + bt * TILE_N, ldzt, colsum);
+    if (db_part != nullptr && lane < 16) {
+        float* o = db_part + (int64_t)bt * ldz + ct * TILE_M + 32 * wave + lane;
+        o[0] = colsum[0];
+        o[16] = colsum[1];
     }
 }
 
-// db[c] = sum over rows of dz[row][c].  A workgroup owns 128 columns; thread (tx, ty) sums four
-// columns over rows ty, ty + 8, ...; the eight row groups are then added through LDS.
-__global__ __launch_bounds__(256) void colsum_db(const uint16_t* __restrict__ dZ, int64_t ldz, int B, int C,
-                                                  float* __restrict__ db) {
-    __shared__ float red[8][128];
-    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
-    const int c0 = blockIdx.x * 128 + tx * 4;
-    float s[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int r = ty; r < B; r += 8) {
-        const u32x2 p = *reinterpret_cast<const u32x2*>(dZ + (int64_t)r * ldz + c0);
-        s[0] += __uint_as_float(p[0] << 16);
-        s[1] += __uint_as_float(p[0] & 0xffff0000u);
-        s[2] += __uint_as_float(p[1] << 16);
-        s[3] += __uint_as_float(p[1] & 0xffff0000u);
-    }
-#pragma unroll
-    for (int e = 0; e < 4; ++e) red[ty][tx * 4 + e] = s[e];
+// db[c] = sum over the row tiles of their column sums.
+__global__ void finish_db(const float* __restrict__ db_part, int nBT, int64_t stride, int C, float* __restrict__ db) {
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= C) return;
+    float s = 0.0f;
+    for (int t = 0; t < nBT; ++t) s += db_part[t * stride + c];
+    db[c] = s;
+}
+
+// XT[d][b] = X[b][d], zero for b >= B (the dW contraction reads whole 64-row k-steps).
+// 64 x 64 tiles through LDS; grid (Bpad / 64, D / 64), 256 threads.
+__global__ __launch_bounds__(256) void transpose_x(const uint16_t* __restrict__ X, int64_t ldx, int B,
+                                                    uint16_t* __restrict__ XT, int64_t ldxt) {
+    __shared__ uint16_t tile[64][66];
+    const int b0 = blockIdx.x * 64, d0 = blockIdx.y * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int r = ty; r < 64; r += 4) tile[r][tx] = (b0 + r < B) ? X[(int64_t)(b0 + r) * ldx + d0 + tx] : (uint16_t)0;
     __syncthreads();
-    if (threadIdx.x < 128) {
-        float t = 0.0f;
-#pragma unroll
-        for (int y = 0; y < 8; ++y) t += red[y][threadIdx.x];
-        const int c = blockIdx.x * 128 + threadIdx.x;
-        if (c < C) db[c] = t;
-    }
+    for (int r = ty; r < 64; r += 4) XT[(int64_t)(d0 + r) * ldxt + b0 + tx] = tile[tx][r];
 }
 
 struct DxArgs {
@@ -362,15 +365,15 @@ __global__ void reduce_dx(const float* __restrict__ parts, int splits, int64_t s
 }
 
 struct DwArgs {
-    const uint16_t* X; int64_t ldx;      // [B][D]
-    const uint16_t* dZ; int64_t ldz;     // [Bpad][Cpad]
-    int B, D, C;
+    const uint16_t* XT; int64_t ldxt;    // [D][Bpad]
+    const uint16_t* dZT; int64_t ldzt;   // [Cpad][Bpad]
+    int D, C;
     int nDT, nCT, k_steps;
     uint16_t* dW; int64_t lddw;
 };
 
-// dW^T tile: M = features d (A = X read k-strided), N = classes (B operand = dz read k-strided),
-// K = batch rows.
+// dW^T tile: M = features d (A = X^T), N = classes (B operand = dz^T), K = batch rows; both operands
+// are contiguous along the rows.
 __global__ __launch_bounds__(NTHREADS) void bwd_dw(DwArgs a) {
     __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
     const int tile = xcd_logical_tile(a.nDT * a.nCT);
@@ -379,29 +382,16 @@ __global__ __launch_bounds__(NTHREADS) void bwd_dw(DwArgs a) {
 
     f32x16 acc[MT][NT];
     zero_acc(acc);
-    Operand A{a.X, a.ldx, a.B - 1, a.D - 8};
-    Operand Bo{a.dZ, a.ldz, INT_MAX, INT_MAX};         // dz is padded to whole tiles: never clamped
-    gemm_mainloop<KS, KS>(acc, A, Bo, dt * TILE_M, ct * TILE_N, 0, a.k_steps, lds);
+    Operand A{a.XT, a.ldxt, a.D - 1, 0};
+    Operand Bo{a.dZT, a.ldzt, INT_MAX, 0};             // dz^T is padded to whole tiles: never clamped
+    gemm_mainloop<KC, KC>(acc, A, Bo, dt * TILE_M, ct * TILE_N, 0, a.k_steps, lds);
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 2, wn = wave & 3, h = lane >> 5, jl = lane & 31;
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        const int c = ct * TILE_N + wn * WAVE_N + 32 * nt + jl;
-        if (c >= a.C) continue;
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-            for (int v4 = 0; v4 < 4; ++v4) {
-                const int d = dt * TILE_M + wm * WAVE_M + 32 * mt + 8 * v4 + 4 * h;
-                if (d < a.D) {
-                    u32x2 p;
-                    p[0] = pack_bf16(acc[mt][nt][4 * v4 + 0], acc[mt][nt][4 * v4 + 1]);
-                    p[1] = pack_bf16(acc[mt][nt][4 * v4 + 2], acc[mt][nt][4 * v4 + 3]);
-                    *reinterpret_cast<u32x2*>(a.dW + (int64_t)c * a.lddw + d) = p;
-                }
-            }
-    }
+    // [class][feature] tile through LDS, then whole 512-byte rows of dW
+    acc_to_lds_bf16(acc, lds);
+    __syncthreads();
+    const int c_left = a.C - ct * TILE_N, d_left = a.D - dt * TILE_M;
+    lds_tile_store_rows(lds, a.dW + (int64_t)ct * TILE_N * a.lddw + dt * TILE_M, a.lddw,
+                        c_left < TILE_N ? c_left : TILE_N, d_left < TILE_M ? d_left : TILE_M);
 }
 
 // ---- host side -----------------------------------------------------------------------------------
@@ -414,7 +404,7 @@ struct BwdPlan {
     int64_t Bpad, Cpad;
     int nBT, nCT, nDT;
     int steps_total, splits, steps_per_split;
-    size_t dz_bytes, parts_bytes;
+    size_t dz_bytes, xt_bytes, dbp_bytes, parts_bytes;     // dz and dz^T take dz_bytes each
 };
 
 static bool shape_ok(int32_t B, int32_t D, int32_t C) { return B > 0 && D > 0 && C > 0 && D % 64 == 0; }
@@ -433,6 +423,8 @@ static BwdPlan plan_bwd(int32_t B, int32_t D, int32_t C) {
     p.steps_per_split = (p.steps_total + want - 1) / want;
     p.splits = (p.steps_total + p.steps_per_split - 1) / p.steps_per_split;
     p.dz_bytes = (size_t)p.Bpad * p.Cpad * 2;
+    p.xt_bytes = (size_t)D * p.Bpad * 2;
+    p.dbp_bytes = (size_t)p.nBT * p.Cpad * 4;
     p.parts_bytes = (size_t)p.splits * B * D * 4;
     return p;
 }
@@ -457,10 +449,10 @@ static int check_fc_common(const void* X, int64_t ldx, const void* W, int64_t ld
 // When enabled, every kernel launch is bracketed by a pair of events recorded on the launch stream.
 // The pairs come from a pool created by ws_profile_enable; when the pool is used up, launches go
 // untimed.  Not thread safe; meant for benchmarks.
-enum KernelId { KID_FWD = 0, KID_MERGE, KID_COMBINE, KID_MEAN, KID_DZ, KID_DB, KID_DX, KID_DXRED, KID_DW, KID_COUNT };
+enum KernelId { KID_FWD = 0, KID_MERGE, KID_COMBINE, KID_MEAN, KID_DZ, KID_DB, KID_DX, KID_DXRED, KID_XT, KID_DW, KID_COUNT };
 static const char* const kKernelNames[KID_COUNT] = {"fwd_logits_stats", "merge_class_tiles", "combine_partials",
-                                                    "mean_loss", "bwd_recompute_dz", "colsum_db", "bwd_dx",
-                                                    "reduce_dx", "bwd_dw"};
+                                                    "mean_loss", "bwd_recompute_dz", "finish_db", "bwd_dx",
+                                                    "reduce_dx", "transpose_x", "bwd_dw"};
 struct ProfState {
     bool on = false;
     int capacity = 0, used = 0;
@@ -520,7 +512,7 @@ size_t ws_fwd_workspace_bytes(int32_t B, int32_t D, int32_t C_shard) {
 size_t ws_bwd_workspace_bytes(int32_t B, int32_t D, int32_t C_shard) {
     if (!shape_ok(B, D, C_shard)) return 0;
     const BwdPlan p = plan_bwd(B, D, C_shard);
-    return p.dz_bytes + p.parts_bytes;
+    return 2 * p.dz_bytes + p.xt_bytes + p.dbp_bytes + p.parts_bytes;
 }
 
 int ws_split_fc_fwd(const void* X, int64_t ldx, const void* W_shard, int64_t ldw, const float* b_shard,
@@ -580,12 +572,15 @@ int ws_split_fc_bwd(const void* X, int64_t ldx, const void* W_shard, int64_t ldw
     if (!aligned(dX_partial, 16) || !aligned(dW_shard, 16) || lddx % 4 || lddw % 8) return WS_ERR_ALIGN;
     if (!aligned(logsumexp, 4) || (db_shard && !aligned(db_shard, 4))) return WS_ERR_ALIGN;
     const BwdPlan p = plan_bwd(B, D, C_shard);
-    if (!workspace || workspace_bytes < p.dz_bytes + p.parts_bytes) return WS_ERR_WORKSPACE;
+    if (!workspace || workspace_bytes < 2 * p.dz_bytes + p.xt_bytes + p.dbp_bytes + p.parts_bytes) return WS_ERR_WORKSPACE;
     if (!aligned(workspace, 16)) return WS_ERR_ALIGN;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     uint16_t* dZ = static_cast<uint16_t*>(workspace);
-    float* parts = reinterpret_cast<float*>(static_cast<char*>(workspace) + p.dz_bytes);
+    uint16_t* dZT = dZ + (size_t)p.Bpad * p.Cpad;
+    uint16_t* XT = dZT + (size_t)p.Bpad * p.Cpad;
+    float* db_part = reinterpret_cast<float*>(static_cast<char*>(workspace) + 2 * p.dz_bytes + p.xt_bytes);
+    float* parts = db_part + (size_t)p.nBT * p.Cpad;
 
     FcArgs a;
     a.X = static_cast<const uint16_t*>(X); a.ldx = ldx;
@@ -594,10 +589,10 @@ int ws_split_fc_bwd(const void* X, int64_t ldx, const void* W_shard, int64_t ldw
     a.B = B; a.D = D; a.C = C_shard; a.class_offset = class_offset;
     a.Bpad = (int)p.Bpad; a.nBT = p.nBT; a.nCT = p.nCT;
     WS_LAUNCH(KID_DZ, bwd_recompute_dz, dim3(xcd_grid(p.nBT * p.nCT)), dim3(NTHREADS), s, a, logsumexp,
-                       grad_scale, dZ, p.Cpad);
+                       grad_scale, dZ, p.Cpad, dZT, p.Bpad, db_shard ? db_part : nullptr);
     if (db_shard)
-        WS_LAUNCH(KID_DB, colsum_db, dim3((unsigned)(p.Cpad / 128)), dim3(256), s, dZ, p.Cpad, B, C_shard,
-                           db_shard);
+        WS_LAUNCH(KID_DB, finish_db, dim3((unsigned)((C_shard + 255) / 256)), dim3(256), s, db_part, p.nBT, p.Cpad,
+                  C_shard, db_shard);
 
     DxArgs x;
     x.dZ = dZ; x.ldz = p.Cpad; x.W = a.W; x.ldw = ldw;
@@ -615,9 +610,11 @@ int ws_split_fc_bwd(const void* X, int64_t ldx, const void* W_shard, int64_t ldw
                            (int64_t)B * D, B, D, dX_partial, lddx, accumulate_dx);
     }
 
+    WS_LAUNCH(KID_XT, transpose_x, dim3((unsigned)(p.Bpad / 64), (unsigned)(D / 64)), dim3(256), s, a.X, ldx, B,
+              XT, p.Bpad);
     DwArgs w;
-    w.X = a.X; w.ldx = ldx; w.dZ = dZ; w.ldz = p.Cpad;
-    w.B = B; w.D = D; w.C = C_shard;
+    w.XT = XT; w.ldxt = p.Bpad; w.dZT = dZT; w.ldzt = p.Bpad;
+    w.D = D; w.C = C_shard;
     w.nDT = p.nDT; w.nCT = p.nCT; w.k_steps = (B + TILE_K - 1) / TILE_K;
     w.dW = static_cast<uint16_t*>(dW_shard); w.lddw = lddw;
     WS_LAUNCH(KID_DW, bwd_dw, dim3(xcd_grid(p.nDT * p.nCT)), dim3(NTHREADS), s, w);
