@@ -305,12 +305,19 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 // ---- output tiles through LDS ------------------------------------------------------------------------
 // The MFMA accumulator layout gives a lane one N index and groups of four consecutive M indices, which
 // makes direct global stores 8 or 16 bytes wide and scattered over 32 rows.  Instead the 256 x 256 tile
-// is rounded to bf16 and laid out in LDS as [n][m] (512 bytes per n, sixteen-byte chunks XOR-swizzled
-// by n & 31; it fills the 128 KiB the main loop no longer needs), then written out row by row.
+// is rounded to bf16 and laid out in LDS as [n][m] (512 bytes per n; it fills the 128 KiB the main loop
+// no longer needs), then written out row by row.  Eight-byte slots are XOR-swizzled by a bit permutation
+// of n chosen so that all three access patterns spread over the banks: the accumulator writes (32
+// consecutive n, one slot), the transposing reads (4 consecutive n x 4 consecutive slots per 16 lanes,
+// n 8 apart between the lane blocks) and the row reads (one n, all slots).
+
+__device__ __forceinline__ int out_tile_swizzle(int n) {
+    return ((n >> 2) & 1) | (((n >> 4) & 1) << 1) | ((n & 1) << 2) | (((n >> 1) & 1) << 3) | (((n >> 3) & 1) << 4);
+}
 
 // Byte offset of element (n, m) in the swizzled tile; m must be a multiple of 4 for 8-byte accesses.
 __device__ __forceinline__ int out_tile_offset(int n, int m) {
-    return n * 512 + ((((m >> 3) ^ n) & 31) << 4) + ((m & 7) << 1);
+    return n * 512 + (((m >> 2) ^ out_tile_swizzle(n)) << 3) + ((m & 3) << 1);
 }
 
 __device__ __forceinline__ void acc_to_lds_bf16(const f32x16 (&acc)[MT][NT], char* lds) {
@@ -342,8 +349,11 @@ __device__ __forceinline__ void lds_tile_store_rows(const char* lds, uint16_t* o
         const int q = tid + NTHREADS * i;
         const int n = q >> 5, cq = q & 31;
         if (n < n_valid && cq * 8 < m_valid) {
-            const u32x4 v = *reinterpret_cast<const u32x4*>(lds + n * 512 + (((cq ^ n) & 31) << 4));
-            *reinterpret_cast<u32x4*>(out + (int64_t)n * ld + cq * 8) = v;
+            // the two 8-byte halves of a 16-byte chunk stay in one chunk, swapped when the swizzle is odd
+            const int g = out_tile_swizzle(n);
+            u32x4 v = *reinterpret_cast<const u32x4*>(lds + n * 512 + ((cq ^ (g >> 1)) << 4));
+            if (g & 1) v = __builtin_shufflevector(v, v, 2, 3, 0, 1);
+            __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(out + (int64_t)n * ld + cq * 8));
         }
     }
 }

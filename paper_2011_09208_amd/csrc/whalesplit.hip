@@ -23,6 +23,7 @@
 namespace ws {
 
 constexpr float NEG_INF = -INFINITY;
+constexpr float LOG2E = 1.4426950408889634f;
 
 __device__ __forceinline__ float xor32(float v) { return __shfl_xor(v, 32, 64); }
 
@@ -101,12 +102,12 @@ __global__ __launch_bounds__(NTHREADS) void fwd_logits_stats(FcArgs a, float* __
                                                               float* __restrict__ part_sum,
                                                               float* __restrict__ label_logit) {
     __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
-    const int tile = xcd_logical_tile(a.nBT * a.nCT);
-    if (tile < 0) return;
-    const int ct = tile / a.nBT, bt = tile % a.nBT;   // batch tiles fastest: neighbours share the W panel
     float* sbias = reinterpret_cast<float*>(lds);          // reused after the main loop
     float* red_m = reinterpret_cast<float*>(lds) + 256;    // [2][256]
     float* red_s = red_m + 512;
+    const int tile = xcd_logical_tile(a.nBT * a.nCT);
+    if (tile < 0) return;
+    const int ct = tile / a.nBT, bt = tile % a.nBT;   // batch tiles fastest: neighbours share the W panel
 
     f32x16 acc[MT][NT];
     logits_tile(acc, a, ct, bt, lds, sbias);
@@ -124,11 +125,12 @@ __global__ __launch_bounds__(NTHREADS) void fwd_logits_stats(FcArgs a, float* __
 #pragma unroll
             for (int v = 0; v < 16; ++v) mx = fmaxf(mx, acc[mt][nt][v]);
         const float ms = (mx == NEG_INF) ? 0.0f : mx;
+        const float shift = -ms * LOG2E;                 // exp(z - m) = exp2(z * log2 e - m * log2 e)
         float s = 0.0f;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) s += __expf(acc[mt][nt][v] - ms);
+            for (int v = 0; v < 16; ++v) s += __builtin_amdgcn_exp2f(fmaf(acc[mt][nt][v], LOG2E, shift));
         merge_ms(mx, s, xor32(mx), xor32(s));            // the other half-wave holds the other classes of this row
         if (h == 0) {
             red_m[wm * 256 + wn * WAVE_N + 32 * nt + jl] = mx;
@@ -223,10 +225,10 @@ __global__ __launch_bounds__(NTHREADS) void bwd_recompute_dz(FcArgs a, const flo
                                                               int64_t ldz, uint16_t* __restrict__ dZT,
                                                               int64_t ldzt, float* __restrict__ db_part) {
     __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
+    float* sbias = reinterpret_cast<float*>(lds);
     const int tile = xcd_logical_tile(a.nBT * a.nCT);
     if (tile < 0) return;
     const int ct = tile / a.nBT, bt = tile % a.nBT;
-    float* sbias = reinterpret_cast<float*>(lds);
 
     f32x16 acc[MT][NT];
     logits_tile(acc, a, ct, bt, lds, sbias);
@@ -241,10 +243,19 @@ __global__ __launch_bounds__(NTHREADS) void bwd_recompute_dz(FcArgs a, const flo
         const bool row_ok = row < a.B;
         const float lse = row_ok ? logsumexp[row] : 0.0f;
         const float g = row_ok ? grad_scale : 0.0f;                    // padded rows store exact zeros
+        // |g| * exp(z - lse) = exp2(z * log2 e + (log2 |g| - lse * log2 e)): one FMA and one exp2 per
+        // element; g = 0 gives a shift of -inf and exact zeros, as does z = -inf on padded classes.
+        const float shift = __log2f(fabsf(g)) - lse * LOG2E;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[mt][nt][v] = g * __expf(acc[mt][nt][v] - lse);   // exp(-inf) = 0 on padded classes
+            for (int v = 0; v < 16; ++v) acc[mt][nt][v] = __builtin_amdgcn_exp2f(fmaf(acc[mt][nt][v], LOG2E, shift));
+        if (grad_scale < 0.0f) {                                        // uniform; the usual scales are positive
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[mt][nt][v] = -acc[mt][nt][v];
+        }
 
         const int local = row_ok ? a.labels[row] - a.class_offset : -1;
         const bool in_shard = local >= 0 && local < a.C;
