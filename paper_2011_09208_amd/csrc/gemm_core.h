@@ -217,13 +217,17 @@ __device__ __forceinline__ void gemm_mainloop(f32x16 (&acc)[MT][NT], const Opera
         quarter_r2s<BKIND>(stage + OPERAND_TILE_BYTES, sb[quarter], tid, quarter);
     };
 
-    // prologue: stage 0 <- k-step 0; quarter 3 of k-step 1 -> stage 1; registers <- what the loop expects
+    // prologue: stage 0 <- k-step 0; quarter 3 of k-step 1 -> stage 1; registers <- what the loop expects.
+    // Quarter 3 of k-step 1 is fetched together with k-step 0 (into spare registers), so the fill costs
+    // one global-memory latency, not two.
 #pragma unroll
     for (int q = 0; q < 4; ++q) g2r(q, 0);
+    const u32x4 a31 = quarter_g2r<AKIND>(A, m0, kofs(1), tid, 3);
+    const u32x4 b31 = quarter_g2r<BKIND>(Bop, n0, kofs(1), tid, 3);
 #pragma unroll
     for (int q = 0; q < 4; ++q) r2s(q, lds);
-    g2r(3, 1);
-    r2s(3, lds + STAGE_BYTES);
+    quarter_r2s<AKIND>(lds + STAGE_BYTES, a31, tid, 3);
+    quarter_r2s<BKIND>(lds + STAGE_BYTES + OPERAND_TILE_BYTES, b31, tid, 3);
 #pragma unroll
     for (int q = 0; q < 3; ++q) g2r(q, 1);
     g2r(3, 2);

@@ -5,12 +5,12 @@
 //                      logit reduced in the epilogue; one (max, sum) partial per 256-class tile
 //   merge_class_tiles  merges those partials into row_max / row_sumexp of the shard
 //   combine_partials   merges the shards' statistics into logsumexp and loss
-//   bwd_recompute_dz   same GEMM again, epilogue dz = g (exp(z - lse) - onehot) stored as bf16,
-//                      both row-major and transposed
-//   finish_db          db = sum over the row tiles of the column sums bwd_recompute_dz produced
-//   bwd_dx             dX_partial = dz . W_s, split along the class contraction; partial sums
-//   reduce_dx          sums the split-K partials (optionally accumulating into the caller's dX)
 //   transpose_x        X^T for the dW contraction
+//   bwd_recompute_dz   same GEMM again, epilogue dz = g (exp(z - lse) - onehot) stored as bf16, both
+//                      row-major and transposed; column sums of the tile (db partials)
+//   bwd_dx             dX_partial = dz . W_s, split along the class contraction; partial sums
+//   finish_bwd         sums the split-K partials of dX (optionally accumulating into the caller's dX)
+//                      and the db partials
 //   bwd_dw             dW_s = dz^T . X
 #include <hip/hip_runtime.h>
 #include <limits.h>
@@ -287,15 +287,6 @@ __global__ __launch_bounds__(NTHREADS) void bwd_recompute_dz(FcArgs a, const flo
     }
 }
 
-// db[c] = sum over the row tiles of their column sums.
-__global__ void finish_db(const float* __restrict__ db_part, int nBT, int64_t stride, int C, float* __restrict__ db) {
-    const int c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c >= C) return;
-    float s = 0.0f;
-    for (int t = 0; t < nBT; ++t) s += db_part[t * stride + c];
-    db[c] = s;
-}
-
 // XT[d][b] = X[b][d], zero for b >= B (the dW contraction reads whole 64-row k-steps).
 // 64 x 64 tiles through LDS; grid (Bpad / 64, D / 64), 256 threads.
 __global__ __launch_bounds__(256) void transpose_x(const uint16_t* __restrict__ X, int64_t ldx, int B,
@@ -357,21 +348,35 @@ __global__ __launch_bounds__(NTHREADS) void bwd_dx(DxArgs a) {
     }
 }
 
-__global__ void reduce_dx(const float* __restrict__ parts, int splits, int64_t split_stride, int B, int D,
-                          float* __restrict__ dX, int64_t lddx, int accumulate) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // one float4 per thread
-    const int d4 = D >> 2;
-    if (i >= (int64_t)B * d4) return;
-    const int row = (int)(i / d4), d = (int)(i % d4) * 4;
-    f32x4 s = {0.f, 0.f, 0.f, 0.f};
-    for (int p = 0; p < splits; ++p) s += *reinterpret_cast<const f32x4*>(parts + p * split_stride + (int64_t)row * D + d);
-    float* o = dX + (int64_t)row * lddx + d;
-    if (accumulate) {
+// Finishes the two small reductions of the backward call in one launch: workgroups [0, dx_blocks) sum
+// the split-K partials of dX in a fixed order (one float4 per thread; optionally accumulating into the
+// caller's dX), the remaining workgroups sum the per-row-tile column sums into db.
+__global__ __launch_bounds__(256) void finish_bwd(const float* __restrict__ parts, int splits, int64_t split_stride,
+                                                   int B, int D, float* __restrict__ dX, int64_t lddx, int accumulate,
+                                                   int dx_blocks, const float* __restrict__ db_part, int nBT,
+                                                   int64_t db_stride, int C, float* __restrict__ db) {
+    if ((int)blockIdx.x < dx_blocks) {
+        const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+        const int d4 = D >> 2;
+        if (i >= (int64_t)B * d4) return;
+        const int row = (int)(i / d4), d = (int)(i % d4) * 4;
+        f32x4 s = {0.f, 0.f, 0.f, 0.f};
+        for (int p = 0; p < splits; ++p)
+            s += *reinterpret_cast<const f32x4*>(parts + p * split_stride + (int64_t)row * D + d);
+        float* o = dX + (int64_t)row * lddx + d;
+        if (accumulate) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] += s[e];
+            for (int e = 0; e < 4; ++e) o[e] += s[e];
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = s[e];
+        }
     } else {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] = s[e];
+        const int c = ((int)blockIdx.x - dx_blocks) * blockDim.x + threadIdx.x;
+        if (c >= C) return;
+        float s = 0.0f;
+        for (int t = 0; t < nBT; ++t) s += db_part[t * db_stride + c];
+        db[c] = s;
     }
 }
 
@@ -460,10 +465,10 @@ static int check_fc_common(const void* X, int64_t ldx, const void* W, int64_t ld
 // When enabled, every kernel launch is bracketed by a pair of events recorded on the launch stream.
 // The pairs come from a pool created by ws_profile_enable; when the pool is used up, launches go
 // untimed.  Not thread safe; meant for benchmarks.
-enum KernelId { KID_FWD = 0, KID_MERGE, KID_COMBINE, KID_MEAN, KID_DZ, KID_DB, KID_DX, KID_DXRED, KID_XT, KID_DW, KID_COUNT };
+enum KernelId { KID_FWD = 0, KID_MERGE, KID_COMBINE, KID_MEAN, KID_XT, KID_DZ, KID_DX, KID_FINISH, KID_DW, KID_COUNT };
 static const char* const kKernelNames[KID_COUNT] = {"fwd_logits_stats", "merge_class_tiles", "combine_partials",
-                                                    "mean_loss", "bwd_recompute_dz", "finish_db", "bwd_dx",
-                                                    "reduce_dx", "transpose_x", "bwd_dw"};
+                                                    "mean_loss", "transpose_x", "bwd_recompute_dz", "bwd_dx",
+                                                    "finish_bwd", "bwd_dw"};
 struct ProfState {
     bool on = false;
     int capacity = 0, used = 0;
@@ -599,11 +604,10 @@ int ws_split_fc_bwd(const void* X, int64_t ldx, const void* W_shard, int64_t ldw
     a.bias = b_shard; a.labels = labels;
     a.B = B; a.D = D; a.C = C_shard; a.class_offset = class_offset;
     a.Bpad = (int)p.Bpad; a.nBT = p.nBT; a.nCT = p.nCT;
+    WS_LAUNCH(KID_XT, transpose_x, dim3((unsigned)(p.Bpad / 64), (unsigned)(D / 64)), dim3(256), s, a.X, ldx, B,
+              XT, p.Bpad);
     WS_LAUNCH(KID_DZ, bwd_recompute_dz, dim3(xcd_grid(p.nBT * p.nCT)), dim3(NTHREADS), s, a, logsumexp,
-                       grad_scale, dZ, p.Cpad, dZT, p.Bpad, db_shard ? db_part : nullptr);
-    if (db_shard)
-        WS_LAUNCH(KID_DB, finish_db, dim3((unsigned)((C_shard + 255) / 256)), dim3(256), s, db_part, p.nBT, p.Cpad,
-                  C_shard, db_shard);
+              grad_scale, dZ, p.Cpad, dZT, p.Bpad, db_shard ? db_part : nullptr);
 
     DxArgs x;
     x.dZ = dZ; x.ldz = p.Cpad; x.W = a.W; x.ldw = ldw;
@@ -615,14 +619,16 @@ int ws_split_fc_bwd(const void* X, int64_t ldx, const void* W_shard, int64_t ldw
     x.ldo = direct ? lddx : D;
     x.split_stride = (int64_t)B * D;
     WS_LAUNCH(KID_DX, bwd_dx, dim3(xcd_grid(p.nDT * p.nBT * p.splits)), dim3(NTHREADS), s, x);
-    if (!direct) {
+    {
         const int64_t n4 = (int64_t)B * (D / 4);
-        WS_LAUNCH(KID_DXRED, reduce_dx, dim3((unsigned)((n4 + 255) / 256)), dim3(256), s, parts, p.splits,
-                           (int64_t)B * D, B, D, dX_partial, lddx, accumulate_dx);
+        const int dx_blocks = direct ? 0 : (int)((n4 + 255) / 256);
+        const int db_blocks = db_shard ? (C_shard + 255) / 256 : 0;
+        if (dx_blocks + db_blocks > 0)
+            WS_LAUNCH(KID_FINISH, finish_bwd, dim3((unsigned)(dx_blocks + db_blocks)), dim3(256), s, parts, p.splits,
+                      (int64_t)B * D, B, D, dX_partial, lddx, accumulate_dx, dx_blocks, db_part, p.nBT, p.Cpad,
+                      C_shard, db_shard);
     }
 
-    WS_LAUNCH(KID_XT, transpose_x, dim3((unsigned)(p.Bpad / 64), (unsigned)(D / 64)), dim3(256), s, a.X, ldx, B,
-              XT, p.Bpad);
     DwArgs w;
     w.XT = XT; w.ldxt = p.Bpad; w.dZT = dZT; w.ldzt = p.Bpad;
     w.D = D; w.C = C_shard;
