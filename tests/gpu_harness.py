@@ -28,12 +28,15 @@ def bf16_to_f64(t: torch.Tensor) -> np.ndarray:
     return inputs.bf16_bits_to_f64(t.view(torch.int16).cpu().numpy().view(np.uint16))
 
 
-def run_step(X_bits, W_bits, bias, labels, shards, g=1.0, w_lo=0, want_db=True, loss_mean=False):
+def run_step(X_bits, W_bits, bias, labels, shards, g=1.0, w_lo=0, want_db=True, loss_mean=False,
+             lse_override=None):
     """fwd on every shard -> combine -> bwd on every shard (dX accumulated across shards).
 
     W_bits holds classes [w_lo, w_lo + rows); `shards` = [(class_offset, C_shard)].
     Returns numpy arrays: per-shard m, s, t [S, B]; lse, loss [B]; dX [B, D];
     dW list of [C_s, D] (float64 upcast of bf16), db list of [C_s].
+    `lse_override` [B] replaces the combined log-sum-exp as the backward call's input (used when only
+    some shards of a wider layer are evaluated).
     """
     from paper_2011_09208_amd import binding as ws
 
@@ -58,6 +61,8 @@ def run_step(X_bits, W_bits, bias, labels, shards, g=1.0, w_lo=0, want_db=True, 
         bs = None if b_dev is None else b_dev[off - w_lo: off - w_lo + c]
         ws.split_fc_fwd(X, Ws, bs, y, off, m[i], s[i], t[i], work)
     ws.combine_partials(m, s, t, lse, loss, mean)
+    lse_bwd = lse if lse_override is None else torch.from_numpy(
+        np.ascontiguousarray(lse_override, dtype=np.float32)).cuda()
     dX = torch.full((B, D), float("nan"), device="cuda")
     dWs, dbs = [], []
     for i, (off, c) in enumerate(shards):
@@ -65,7 +70,7 @@ def run_step(X_bits, W_bits, bias, labels, shards, g=1.0, w_lo=0, want_db=True, 
         bs = None if b_dev is None else b_dev[off - w_lo: off - w_lo + c]
         dW = torch.full((c, D), float("nan"), device="cuda", dtype=torch.bfloat16)
         db = torch.full((c,), float("nan"), device="cuda") if want_db else None
-        ws.split_fc_bwd(X, Ws, bs, lse, y, off, g, dX, i > 0, dW, db, work)
+        ws.split_fc_bwd(X, Ws, bs, lse_bwd, y, off, g, dX, i > 0, dW, db, work)
         dWs.append(dW)
         dbs.append(db)
     torch.cuda.synchronize()

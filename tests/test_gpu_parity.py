@@ -153,3 +153,37 @@ def test_full_size_workloads(H, name):
     """The paper-shaped workloads at full size, every output compared element by element."""
     p = inputs.make_config(name)
     _full_parity(H, p, p.shards, tag=name)
+
+
+def test_large_vocab_head_shard(H):
+    """cfg5 at full size: B = 8192 token rows, D = 1024, the first 50 000 of 400 000 classes, Zipf labels
+    (most of them inside this shard).  Only this shard is evaluated, as bench.py times it: its forward
+    statistics are compared with the oracle's for every row, and the backward call is given a
+    log-sum-exp the oracle makes up for the missing seven shards (the shard's own plus ln 8, i.e. equal
+    mass in every shard) and compared element by element with the oracle's definition of the shard's
+    gradients for that input."""
+    from oracle import oracle
+    p = inputs.make_config("cfg5", w_rows=50_000)
+    off, c = 0, 50_000
+    H.say(f"[parity] cfg5 shard: B={p.B} D={p.D} C_shard={c} of {p.C}")
+    X = inputs.bf16_bits_to_f64(p.X_bits)
+    W = inputs.bf16_bits_to_f64(p.W_bits)
+    y = p.labels.astype(np.int64)
+    m, s, t = oracle.partials(X, W, None, y, off)
+    lse_in = (m + np.log(s) + math.log(8.0)).astype(np.float32)          # an input, rounded once to fp32
+    g = 1.0 / p.B
+    got = H.run_step(p.X_bits, p.W_bits, None, p.labels, [(off, c)], g=g, lse_override=lse_in)
+    inside = (y >= off) & (y < off + c)
+    assert 0.8 < inside.mean() < 0.9
+    assert np.all(got["t"][0][~inside] == 0.0)
+    zscale = max(1.0, float(np.max(np.abs(m))))
+    assert np.max(np.abs(got["m"][0] - m)) <= H.LSE_ABS * zscale
+    assert np.max(np.abs(got["s"][0] - s) / s) <= 1e-3 + H.LSE_ABS * zscale
+    assert np.max(np.abs(got["t"][0] - t)) <= H.LSE_ABS * zscale
+    ref = oracle.shard_grads(X, W, None, lse_in.astype(np.float64), y, off, g)
+    rep = {k: H.max_rel_to_max(a, b) for k, a, b in (("dX", got["dX"], ref["dX_partial"]),
+                                                      ("dW", got["dW"][0], ref["dW"]),
+                                                      ("db", got["db"][0], ref["db"]))}
+    H.say("[parity] cfg5 shard: " + " ".join(f"{k}={v:.2e}" for k, v in rep.items()))
+    for k, v in rep.items():
+        assert v <= H.GRAD_REL_TO_MAX, (k, v)
