@@ -128,6 +128,24 @@ int ws_split_fc_bwd(const void* X, int64_t ldx,
                     float* db_shard,
                     void* workspace, size_t workspace_bytes, void* stream);
 
+/* Hardware-aware shard widths (HOST pointers only; no GPU work).  Section 3.3.1: a `split`
+ * TaskGraph is balanced over devices of unequal capacity by uneven sharding in the splitting
+ * dimension; load ratios proportional to the devices' FLOP/s minimise the formula given there,
+ * and Algorithm 1 (Memory-Constraint Load Balancing) then shifts load from the over-memory device
+ * with the highest memory utilisation to the device with room that has the lowest (FLOP
+ * utilisation, memory utilisation), until no device is over memory or none has room.
+ * Here the unit of load is one class column: device i with width w_i uses (w_i / C) TG_mem of
+ * memory and (w_i / C) TG_flop of work.  Initial widths are the proportional shares rounded by
+ * largest remainder; a shift moves the smaller of what the peak must shed and what the valley can
+ * take; ties go to the lower device index.
+ *   DF[N]  FLOP/s of each device        DM[N]  memory capacity of each device
+ *   TG_flop, TG_mem   work and peak memory of the whole layer (same units as DF, DM)
+ *   widths[N] out: non-negative, sum = C    feasible out: 1 if every device fits its memory, else 0
+ * WS_ERR_NULL / WS_ERR_SHAPE (N, C <= 0) / WS_ERR_RANGE (a non-positive or non-finite quantity).
+ */
+int ws_balance_widths(int32_t N, const double* DF, const double* DM, double TG_flop, double TG_mem,
+                      int32_t C, int32_t* widths, int32_t* feasible);
+
 /* Optional per-kernel timing, for benchmarks (not part of the paper's method; host-side state,
  * not thread safe).  ws_profile_enable(n) creates a pool of n event pairs (n <= 0 switches
  * timing off and frees the pool); while the pool lasts, every kernel the library launches is

@@ -49,10 +49,14 @@ lib.ws_profile_kernel_name.argtypes = [_i32]
 lib.ws_profile_read.restype = ctypes.c_int
 lib.ws_profile_read.argtypes = [_i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
 
+lib.ws_balance_widths.restype = ctypes.c_int
+lib.ws_balance_widths.argtypes = [_i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
+                                  ctypes.c_double, ctypes.c_double, _i32, ctypes.POINTER(_i32), ctypes.POINTER(_i32)]
+
 EXPORTS = ["ws_status_string", "ws_version", "ws_fwd_workspace_bytes", "ws_split_fc_fwd",
            "ws_combine_partials", "ws_bwd_workspace_bytes", "ws_split_fc_bwd",
            "ws_profile_enable", "ws_profile_reset", "ws_profile_kernel_count", "ws_profile_kernel_name",
-           "ws_profile_read"]
+           "ws_profile_read", "ws_balance_widths"]
 
 
 class WhaleSplitError(RuntimeError):
@@ -141,3 +145,14 @@ def profile_read():
         if n.value:
             out[lib.ws_profile_kernel_name(k).decode()] = (ms.value, n.value)
     return out
+
+
+def balance_widths(C, DF, DM, TG_flop, TG_mem):
+    """Shard widths for devices with FLOP/s DF and memory DM; returns (list of widths, feasible)."""
+    n = len(DF)
+    df = (ctypes.c_double * n)(*[float(v) for v in DF])
+    dm = (ctypes.c_double * n)(*[float(v) for v in DM])
+    w = (_i32 * n)()
+    ok = _i32(0)
+    _check(lib.ws_balance_widths(n, df, dm, float(TG_flop), float(TG_mem), int(C), w, ctypes.byref(ok)))
+    return list(w), bool(ok.value)
