@@ -187,3 +187,50 @@ def test_large_vocab_head_shard(H):
     H.say("[parity] cfg5 shard: " + " ".join(f"{k}={v:.2e}" for k, v in rep.items()))
     for k, v in rep.items():
         assert v <= H.GRAD_REL_TO_MAX, (k, v)
+
+
+def test_padded_pitches_stream_and_accumulate(H):
+    """Row pitches larger than the row length for every matrix argument, a side stream, loss_mean, and
+    accumulate_dx on top of a pre-filled dX: the library must honour pitches, touch nothing in the padding,
+    enqueue on the stream it is given, and add to (not overwrite) dX when asked."""
+    import torch
+    from oracle import oracle
+    from paper_2011_09208_amd import binding as ws
+    B, D, C = 200, 128, 700
+    p = inputs.make_inputs("pitch", B, D, C, w_sigma=0.3, bias_sigma=0.7, seed=21)
+    H.say(f"[parity] padded pitches on a side stream: B={B} D={D} C={C}")
+    dev = torch.device("cuda")
+    PX, PW, PDX, PDW = D + 64, D + 8, D + 12, D + 24
+    Xp = torch.full((B, PX), float("nan"), device=dev, dtype=torch.bfloat16)
+    Xp[:, :D] = H.dev_bf16(p.X_bits)
+    Wp = torch.full((C, PW), float("nan"), device=dev, dtype=torch.bfloat16)
+    Wp[:, :D] = H.dev_bf16(p.W_bits)
+    X, W = Xp[:, :D], Wp[:, :D]
+    bias = torch.from_numpy(p.bias).to(dev)
+    y = torch.from_numpy(p.labels).to(dev)
+    m, s, t = (torch.empty((1, B), device=dev) for _ in range(3))
+    lse, loss, mean = torch.empty(B, device=dev), torch.empty(B, device=dev), torch.empty(1, device=dev)
+    dXp = torch.full((B, PDX), 7.0, device=dev)
+    dWp = torch.full((C, PDW), 3.0, device=dev, dtype=torch.bfloat16)
+    db = torch.empty(C, device=dev)
+    work = torch.empty(max(ws.fwd_workspace_bytes(B, D, C), ws.bwd_workspace_bytes(B, D, C)), dtype=torch.uint8,
+                       device=dev)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        ws.split_fc_fwd(X, W, bias, y, 0, m[0], s[0], t[0], work)
+        ws.combine_partials(m, s, t, lse, loss, mean)
+        ws.split_fc_bwd(X, W, bias, lse, y, 0, 0.5, dXp[:, :D], True, dWp[:, :D], db, work)
+    side.synchronize()
+    ref = oracle.unsharded(inputs.bf16_bits_to_f64(p.X_bits), inputs.bf16_bits_to_f64(p.W_bits),
+                           p.bias.astype(np.float64), p.labels, 0.5)
+    assert np.max(np.abs(lse.cpu().numpy() - ref["lse"])) <= H.LSE_ABS * max(1.0, np.abs(ref["lse"]).max())
+    assert abs(float(mean.cpu()[0]) - ref["loss_mean"]) <= 1e-3 * ref["loss_mean"]
+    dX = dXp.cpu().numpy()
+    assert np.all(dX[:, D:] == 7.0)                                   # padding untouched
+    assert H.max_rel_to_max(dX[:, :D] - 7.0, ref["dX"]) <= H.GRAD_REL_TO_MAX + 1e-5    # accumulated on top of 7
+    dW = dWp.float().cpu().numpy()
+    assert np.all(dW[:, D:] == 3.0)
+    assert H.max_rel_to_max(dW[:, :D].astype(np.float64), ref["dW"]) <= H.GRAD_REL_TO_MAX
+    assert H.max_rel_to_max(db.cpu().numpy(), ref["db"]) <= H.GRAD_REL_TO_MAX
+    assert torch.isnan(Xp[:, D:]).all() and torch.isnan(Wp[:, D:]).all()      # inputs never modified
