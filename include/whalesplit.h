@@ -30,7 +30,9 @@
  *
  * Errors.  Every entry point returns a ws_status.  Arguments are validated on the
  * host before any HIP call, so the WS_ERR_NULL/SHAPE/ALIGN/RANGE/WORKSPACE paths
- * need no GPU.  Requirements: B, D, C_shard > 0; D a multiple of 64; pitches >= D
+ * need no GPU.  Requirements: B, D, C_shard > 0; D a multiple of 64; every matrix (and the
+ * backward call's bf16 dz scratch, 2 * roundup(B, 256) * roundup(C_shard, 256) bytes) below 4 GiB
+ * with 256 rows to spare, as the kernels use 32-bit offsets (else WS_ERR_SHAPE); pitches >= D
  * (>= C for the statistics stride) and multiples of 8 elements; matrix base
  * pointers 16-byte aligned, fp32/int32 vectors 4-byte aligned;
  * class_offset >= 0 and class_offset + C_shard <= INT32_MAX.  Labels live on the

@@ -3,7 +3,9 @@
 //
 // One workgroup of 512 threads (8 wave64s, two per SIMD) owns a 256 x 256 output tile
 // and walks the contraction in steps of 64.  The waves form a 2 (M) x 4 (N) grid; each
-// owns a 128 x 64 sub-tile held as 4 x 2 accumulators of v_mfma_f32_32x32x16_bf16.
+// owns a 128 x 64 sub-tile held as 8 x 4 accumulators of v_mfma_f32_16x16x32_bf16 (measured
+// about 7 % faster than the 32x32x16 form under the chip's power limit: it moves half as many
+// accumulator registers per flop).
 //
 // An operand tile is staged in LDS in one of two layouts, chosen by how the operand
 // lies in memory relative to the contraction index k:
@@ -11,11 +13,11 @@
 //       16-byte chunks XOR-swizzled by (row >> 1) & 7); a lane's MFMA fragment (8
 //       consecutive k of one row) is one ds_read_b128.
 //   KS ("k strided"):    memory is [k][col]; LDS holds [64 k][256 cols] (512 B per k-row,
-//       16-byte chunks XOR-swizzled by (k & 3) << 2); the fragment is gathered with two
-//       ds_read_b64_tr_b16 transpose reads (4 consecutive k of one column each).
-// Lane layouts used (checked on the hardware): for v_mfma_f32_32x32x16_bf16 lane l
-// supplies row l % 32, k = 8 * (l / 32) .. + 7 of either operand; accumulator register v
-// of lane l is element (8 * (v / 4) + 4 * (l / 32) + v % 4, l % 32).  ds_read_b64_tr_b16
+//       16-byte chunks XOR-swizzled by ((k >> 3) & 3) << 1 | (k & 3) << 3); the fragment is
+//       gathered with two ds_read_b64_tr_b16 transpose reads (4 consecutive k of one column each).
+// Lane layouts used (checked on the hardware): for v_mfma_f32_16x16x32_bf16 lane l
+// supplies row l % 16, k = 8 * (l / 16) .. + 7 of either operand; accumulator register v
+// of lane l is element (4 * (l / 16) + v, l % 16).  ds_read_b64_tr_b16
 // works on blocks of 16 lanes: lane i of a block receives, as element e, the (i % 4)-th
 // 16-bit value of the 8 bytes addressed by lane 4 * e + i / 4 of the same block.
 #pragma once
@@ -26,7 +28,6 @@ namespace ws {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
@@ -40,47 +41,59 @@ constexpr int TILE_K = 64;
 constexpr int NTHREADS = 512;
 constexpr int WAVE_M = 128;     // rows of the output tile one wave owns
 constexpr int WAVE_N = 64;
-constexpr int MT = WAVE_M / 32; // 32 x 32 MFMA tiles per wave along M
-constexpr int NT = WAVE_N / 32;
+constexpr int MT = WAVE_M / 16; // 16 x 16 MFMA tiles per wave along M: 8
+constexpr int NT = WAVE_N / 16; // and along N: 4
 constexpr int OPERAND_TILE_BYTES = 256 * TILE_K * 2;           // 32 KiB
 constexpr int STAGE_BYTES = 2 * OPERAND_TILE_BYTES;            // A + B
 constexpr int LDS_BYTES = 2 * STAGE_BYTES;                     // double buffered: 128 KiB
 
 enum { KC = 0, KS = 1 };
 
-// Description of one GEMM operand in global memory (16-bit elements).
-//   KC: element (row, k) at base[row * ld + k];  `row_max` = last valid row (rows beyond are
-//       clamped to it, so the loads stay in bounds and the caller masks the results).
-//   KS: element (k, col) at base[k * ld + col];  `k_max` = last valid k-row (clamped; the
-//       other operand must be zero there), `col_max8` = last valid 8-element chunk start.
+// One GEMM operand in global memory (16-bit elements), addressed through a buffer resource:
+//   KC: element (row, k) at base[row * ld + k];   KS: element (k, col) at base[k * ld + col].
+// Loads are buffer_load_dwordx4 with a scalar resource, a scalar offset (the k-step and the tile
+// quarter) and ONE 32-bit per-lane offset per operand that never changes inside the main loop.
+// The resource covers exactly rows x cols of the matrix: a tile may hang over its end (ragged row or
+// class counts, the last k-step of a contraction) and the overhang reads as zeros, as the hardware
+// bounds check returns 0 beyond the resource.  Offsets are 32-bit: (rows + 256) * ld * 2 bytes must stay
+// below 4 GiB (checked on the host).
 struct Operand {
-    const uint16_t* base;
-    int64_t ld;
-    int lim0;   // KC: row_max      KS: k_max
-    int lim1;   // KC: unused       KS: col_max8
+    __amdgpu_buffer_rsrc_t rsrc;
+    uint32_t ld;        // row pitch in elements
 };
+
+// `rows` x `cols` elements are valid (KC: rows x k extent; KS: k extent x columns).
+__device__ __forceinline__ Operand make_operand(const uint16_t* base, int64_t ld, int64_t rows, int64_t cols) {
+    const int64_t bytes = ((rows - 1) * ld + cols) * 2;
+    Operand op;
+    op.rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(base), 0, (int)(uint32_t)bytes, 0x00020000);
+    op.ld = (uint32_t)ld;
+    return op;
+}
 
 // ---- global -> registers -> LDS staging ---------------------------------------------------
 // A 32 KiB operand tile is 2048 chunks of 16 bytes; thread t moves chunks t, t + 512, t + 1024 and
 // t + 1536.  Chunk set j (one chunk per thread) is "quarter j" of the tile: rows 64 j .. 64 j + 63 of
 // a KC tile, k-rows 16 j .. 16 j + 15 of a KS tile.
 
+// Chunk swizzle of a KS tile: the transposing reads of one wave touch 4 k-rows (k & 3) in each of 4
+// lane blocks 8 k-rows apart ((k >> 3) & 3), two adjacent chunks each: 32 different chunks.
+__device__ __forceinline__ int ks_swizzle(int k) { return (((k >> 3) & 3) << 1) | ((k & 3) << 3); }
+
+// Per-lane byte offset of a thread's chunk in quarter 0 of the tile whose first row (KC) or first
+// column (KS) is o0, at k = 0.
 template <int KIND>
-__device__ __forceinline__ u32x4 quarter_g2r(const Operand& op, int o0, int k0, int tid, int j) {
-    const int q = tid + NTHREADS * j;
-    if (KIND == KC) {
-        const int row = q >> 3, ch = q & 7;
-        int r = o0 + row;
-        r = r < op.lim0 ? r : op.lim0;
-        return *reinterpret_cast<const u32x4*>(op.base + (int64_t)r * op.ld + k0 + ch * 8);
-    } else {
-        const int kr = q >> 5, ch = q & 31;
-        int k = k0 + kr;
-        k = k < op.lim0 ? k : op.lim0;
-        int c = o0 + ch * 8;
-        c = c < op.lim1 ? c : op.lim1;
-        return *reinterpret_cast<const u32x4*>(op.base + (int64_t)k * op.ld + c);
-    }
+__device__ __forceinline__ uint32_t tile_lane_offset(const Operand& op, int o0, int tid) {
+    if (KIND == KC) return ((uint32_t)(o0 + (tid >> 3)) * op.ld + (uint32_t)((tid & 7) * 8)) * 2u;
+    return ((uint32_t)(tid >> 5) * op.ld + (uint32_t)(o0 + (tid & 31) * 8)) * 2u;
+}
+
+// Loads this thread's chunk of quarter j of the tile at contraction offset k0.
+template <int KIND>
+__device__ __forceinline__ u32x4 quarter_g2r(const Operand& op, uint32_t lane_off, int k0, int j) {
+    const uint32_t soff = KIND == KC ? ((uint32_t)k0 + (uint32_t)(64 * j) * op.ld) * 2u
+                                     : ((uint32_t)(k0 + 16 * j) * op.ld) * 2u;
+    return __builtin_amdgcn_raw_buffer_load_b128(op.rsrc, (int)lane_off, (int)soff, 0);
 }
 
 template <int KIND>
@@ -92,7 +105,7 @@ __device__ __forceinline__ void quarter_r2s(char* lds, const u32x4& v, int tid, 
         off = row * 128 + ((ch ^ ((row >> 1) & 7)) << 4);
     } else {
         const int kr = q >> 5, ch = q & 31;
-        off = kr * 512 + ((ch ^ ((kr & 3) << 2)) << 4);
+        off = kr * 512 + ((ch ^ ks_swizzle(kr)) << 4);
     }
     *reinterpret_cast<u32x4*>(lds + off) = v;
 }
@@ -102,34 +115,33 @@ __device__ __forceinline__ void quarter_r2s(char* lds, const u32x4& v, int tid, 
 // Per-lane byte offsets into an operand tile, computed once per kernel.
 template <int KIND, int NTILES>
 struct FragAddr {
-    int off[KIND == KC ? 4 : NTILES];   // KC: one per k-substep; KS: one per 32-wide tile
+    int off[KIND == KC ? 2 : NTILES];   // KC: one per 32-wide k-substep; KS: one per 16-wide tile
 
     // `w0` = first row/column of this wave's sub-tile inside the 256-wide operand tile.
     __device__ __forceinline__ void init(int lane, int w0) {
+        const int i = lane & 15, g = lane >> 4;
         if (KIND == KC) {
-            const int r = lane & 31, h = lane >> 5;
-            const int sw = (r >> 1) & 7;            // w0 and 32 * t are multiples of 32: no effect on the swizzle
+            const int sw = (i >> 1) & 7;            // w0 and 16 * t are multiples of 16: no effect on the swizzle
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) off[ks] = (w0 + r) * 128 + (((2 * ks + h) ^ sw) << 4);
+            for (int s = 0; s < 2; ++s) off[s] = (w0 + i) * 128 + (((4 * s + g) ^ sw) << 4);
         } else {
-            const int x = (lane & 15) >> 2;          // k-row within the group of four == (k & 3)
-            const int krow = 8 * (lane >> 5) + x;
+            const int x = i >> 2;                    // k-row within the group of four == (k & 3)
+            const int krow = 8 * g + x;              // (krow >> 3) & 3 == g; substeps add multiples of 32
 #pragma unroll
             for (int t = 0; t < NTILES; ++t) {
-                const int col = w0 + 32 * t + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-                const int ch = col >> 3;
-                off[t] = krow * 512 + ((ch ^ (x << 2)) << 4) + ((col & 7) << 1);
+                const int col = w0 + 16 * t + 4 * (i & 3);
+                off[t] = krow * 512 + (((col >> 3) ^ ks_swizzle(krow)) << 4) + ((col & 7) << 1);
             }
         }
     }
 
-    // Fragment of 32-wide tile t for k-substep ks (16 k each) from the operand tile at `lds`.
-    __device__ __forceinline__ bf16x8 load(const char* lds, int t, int ks) const {
+    // Fragment of 16-wide tile t for k-substep s (32 k each) from the operand tile at `lds`.
+    __device__ __forceinline__ bf16x8 load(const char* lds, int t, int s) const {
         if (KIND == KC) {
-            return *reinterpret_cast<const bf16x8*>(lds + off[ks] + t * (32 * 128));
+            return *reinterpret_cast<const bf16x8*>(lds + off[s] + t * (16 * 128));
         } else {
             typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
-            const char* p = lds + off[t] + ks * (16 * 512);
+            const char* p = lds + off[t] + s * (32 * 512);
             s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p));
             s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 4 * 512));
             s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -165,8 +177,9 @@ struct SlotSched {
 // Ends with a workgroup barrier, so LDS may be reused by the caller right away.
 //
 // Software pipeline.  LDS holds two stages (k-step j in stage j & 1).  Iteration j multiplies
-// k-step j in four slots of 8 MFMAs each (one per 16-wide k-substep); the fragments of a substep
-// are read from LDS one slot ahead.  The tiles are staged through registers one quarter at a time,
+// k-step j in four slots of 16 MFMAs each: (k-substep 0 | 1 of 32) x (upper | lower 64 rows of the
+// wave's sub-tile); the fragments of a slot are read from LDS one slot ahead (A fragments every slot,
+// B fragments every other slot).  The tiles are staged through registers one quarter at a time,
 // so that LDS writes and global loads are spread evenly over the iteration and every global load
 // has a full iteration to land:
 //   slot x = 0, 1, 2:  quarter x of k-step j + 1: registers -> stage (j + 1) & 1; then the same
@@ -174,16 +187,21 @@ struct SlotSched {
 //   barrier            (every wave has finished reading stage j & 1 and writing stage (j + 1) & 1)
 //   slot 3:            quarter 3 of k-step j + 2: registers -> stage j & 1 (free now); then the
 //                      registers <- quarter 3 of k-step j + 3
-// k-steps beyond the last are clamped to the last one (a harmless reload).
+// k-steps beyond the last are clamped to the last one (a harmless reload).  Rows, columns or k beyond
+// an operand's extent read as zeros.
+typedef f32x4 acc_t[MT][NT];
+
 template <int AKIND, int BKIND>
-__device__ __forceinline__ void gemm_mainloop(f32x16 (&acc)[MT][NT], const Operand& A, const Operand& Bop,
+__device__ __forceinline__ void gemm_mainloop(acc_t& acc, const Operand& A, const Operand& Bop,
                                               int m0, int n0, int k_begin, int k_steps, char* lds) {
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int wm = wave >> 2, wn = wave & 3;
-    constexpr int NDSR = MT * (AKIND == KC ? 1 : 2) + NT * (BKIND == KC ? 1 : 2);
-    constexpr int NMFMA = MT * NT;
+    constexpr int HM = MT / 2;                                   // M tiles per slot
+    constexpr int RA = HM * (AKIND == KC ? 1 : 2);               // LDS reads for a slot's A fragments
+    constexpr int RB = NT * (BKIND == KC ? 1 : 2);               // and for a substep's B fragments
+    constexpr int NMFMA = HM * NT;
     const int last = k_steps - 1;
 
     FragAddr<AKIND, MT> fa;
@@ -192,25 +210,30 @@ __device__ __forceinline__ void gemm_mainloop(f32x16 (&acc)[MT][NT], const Opera
     fb.init(lane, wn * WAVE_N);
 
     u32x4 sa[4], sb[4];
-    bf16x8 af[2][MT], bfr[2][NT];
+    bf16x8 af[2][HM], bfr[2][NT];
 
-    auto load_frags = [&](int set, const char* la, int ks) {
+    auto load_a = [&](int set, const char* la, int s, int half) {
 #pragma unroll
-        for (int t = 0; t < MT; ++t) af[set][t] = fa.load(la, t, ks);
-#pragma unroll
-        for (int t = 0; t < NT; ++t) bfr[set][t] = fb.load(la + OPERAND_TILE_BYTES, t, ks);
+        for (int t = 0; t < HM; ++t) af[set][t] = fa.load(la, HM * half + t, s);
     };
-    auto mfmas = [&](int set) {
+    auto load_b = [&](int set, const char* la, int s) {
 #pragma unroll
-        for (int i = 0; i < MT; ++i)
+        for (int t = 0; t < NT; ++t) bfr[set][t] = fb.load(la + OPERAND_TILE_BYTES, t, s);
+    };
+    auto mfmas = [&](int aset, int bset, int half) {
+#pragma unroll
+        for (int i = 0; i < HM; ++i)
 #pragma unroll
             for (int j = 0; j < NT; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[set][i], bfr[set][j], acc[i][j], 0, 0, 0);
+                acc[HM * half + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[aset][i], bfr[bset][j],
+                                                                                acc[HM * half + i][j], 0, 0, 0);
     };
     auto kofs = [&](int step) { return k_begin + (step < last ? step : last) * TILE_K; };
+    const uint32_t a_off = tile_lane_offset<AKIND>(A, m0, tid);
+    const uint32_t b_off = tile_lane_offset<BKIND>(Bop, n0, tid);
     auto g2r = [&](int quarter, int step) {
-        sa[quarter] = quarter_g2r<AKIND>(A, m0, kofs(step), tid, quarter);
-        sb[quarter] = quarter_g2r<BKIND>(Bop, n0, kofs(step), tid, quarter);
+        sa[quarter] = quarter_g2r<AKIND>(A, a_off, kofs(step), quarter);
+        sb[quarter] = quarter_g2r<BKIND>(Bop, b_off, kofs(step), quarter);
     };
     auto r2s = [&](int quarter, char* stage) {
         quarter_r2s<AKIND>(stage, sa[quarter], tid, quarter);
@@ -222,8 +245,8 @@ __device__ __forceinline__ void gemm_mainloop(f32x16 (&acc)[MT][NT], const Opera
     // one global-memory latency, not two.
 #pragma unroll
     for (int q = 0; q < 4; ++q) g2r(q, 0);
-    const u32x4 a31 = quarter_g2r<AKIND>(A, m0, kofs(1), tid, 3);
-    const u32x4 b31 = quarter_g2r<BKIND>(Bop, n0, kofs(1), tid, 3);
+    const u32x4 a31 = quarter_g2r<AKIND>(A, a_off, kofs(1), 3);
+    const u32x4 b31 = quarter_g2r<BKIND>(Bop, b_off, kofs(1), 3);
 #pragma unroll
     for (int q = 0; q < 4; ++q) r2s(q, lds);
     quarter_r2s<AKIND>(lds + STAGE_BYTES, a31, tid, 3);
@@ -232,60 +255,64 @@ __device__ __forceinline__ void gemm_mainloop(f32x16 (&acc)[MT][NT], const Opera
     for (int q = 0; q < 3; ++q) g2r(q, 1);
     g2r(3, 2);
     __syncthreads();
-    load_frags(0, lds, 0);
+    load_a(0, lds, 0, 0);
+    load_b(0, lds, 0);
 
     for (int j = 0; j < last; ++j) {
         char* lc = lds + (j & 1) * STAGE_BYTES;          // stage of k-step j
         char* ln = lds + ((j + 1) & 1) * STAGE_BYTES;    // stage of k-step j + 1
-        // slot 0
-        load_frags(1, lc, 1);
-        mfmas(0);
+        // slot 0: substep 0, upper rows
+        load_a(1, lc, 0, 1);
+        mfmas(0, 0, 0);
         r2s(0, ln);
         g2r(0, j + 2);
-        SlotSched<0, NMFMA, NDSR, 2, 2>::apply();
-        // slot 1
-        load_frags(0, lc, 2);
-        mfmas(1);
+        SlotSched<0, NMFMA, RA, 2, 2>::apply();
+        // slot 1: substep 0, lower rows
+        load_a(0, lc, 1, 0);
+        load_b(1, lc, 1);
+        mfmas(1, 0, 1);
         r2s(1, ln);
         g2r(1, j + 2);
-        SlotSched<0, NMFMA, NDSR, 2, 2>::apply();
-        // slot 2
-        load_frags(1, lc, 3);
-        mfmas(0);
+        SlotSched<0, NMFMA, RA + RB, 2, 2>::apply();
+        // slot 2: substep 1, upper rows
+        load_a(1, lc, 1, 1);
+        mfmas(0, 1, 0);
         r2s(2, ln);
         g2r(2, j + 2);
-        SlotSched<0, NMFMA, NDSR, 2, 2>::apply();
+        SlotSched<0, NMFMA, RA, 2, 2>::apply();
         __syncthreads();
-        // slot 3
-        load_frags(0, ln, 0);
-        mfmas(1);
+        // slot 3: substep 1, lower rows
+        load_a(0, ln, 0, 0);
+        load_b(0, ln, 0);
+        mfmas(1, 1, 1);
         r2s(3, lc);
         g2r(3, j + 3);
-        SlotSched<0, NMFMA, NDSR, 2, 2>::apply();
+        SlotSched<0, NMFMA, RA + RB, 2, 2>::apply();
     }
     {   // last k-step: nothing left to stage
         const char* lc = lds + (last & 1) * STAGE_BYTES;
-        load_frags(1, lc, 1);
-        mfmas(0);
-        SlotSched<0, NMFMA, NDSR, 0, 0>::apply();
-        load_frags(0, lc, 2);
-        mfmas(1);
-        SlotSched<0, NMFMA, NDSR, 0, 0>::apply();
-        load_frags(1, lc, 3);
-        mfmas(0);
-        SlotSched<0, NMFMA, NDSR, 0, 0>::apply();
-        mfmas(1);
+        load_a(1, lc, 0, 1);
+        mfmas(0, 0, 0);
+        SlotSched<0, NMFMA, RA, 0, 0>::apply();
+        load_a(0, lc, 1, 0);
+        load_b(1, lc, 1);
+        mfmas(1, 0, 1);
+        SlotSched<0, NMFMA, RA + RB, 0, 0>::apply();
+        load_a(1, lc, 1, 1);
+        mfmas(0, 1, 0);
+        SlotSched<0, NMFMA, RA, 0, 0>::apply();
+        mfmas(1, 1, 1);
     }
     __syncthreads();
 }
 
-__device__ __forceinline__ void zero_acc(f32x16 (&acc)[MT][NT]) {
+__device__ __forceinline__ void zero_acc(acc_t& acc) {
 #pragma unroll
     for (int i = 0; i < MT; ++i)
 #pragma unroll
         for (int j = 0; j < NT; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+            for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.0f;
 }
 
 // Workgroups are handed to the 8 XCDs round-robin by their linear id; each XCD has its own L2.
@@ -308,7 +335,7 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 
 // ---- output tiles through LDS ------------------------------------------------------------------------
 // The MFMA accumulator layout gives a lane one N index and groups of four consecutive M indices, which
-// makes direct global stores 8 or 16 bytes wide and scattered over 32 rows.  Instead the 256 x 256 tile
+// makes direct global stores 8 or 16 bytes wide and scattered over 16 rows.  Instead the 256 x 256 tile
 // is rounded to bf16 and laid out in LDS as [n][m] (512 bytes per n; it fills the 128 KiB the main loop
 // no longer needs), then written out row by row.  Eight-byte slots are XOR-swizzled by a bit permutation
 // of n chosen so that all three access patterns spread over the banks: the accumulator writes (32
@@ -324,21 +351,19 @@ __device__ __forceinline__ int out_tile_offset(int n, int m) {
     return n * 512 + (((m >> 2) ^ out_tile_swizzle(n)) << 3) + ((m & 3) << 1);
 }
 
-__device__ __forceinline__ void acc_to_lds_bf16(const f32x16 (&acc)[MT][NT], char* lds) {
+__device__ __forceinline__ void acc_to_lds_bf16(const acc_t& acc, char* lds) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 2, wn = wave & 3, h = lane >> 5, jl = lane & 31;
+    const int wm = wave >> 2, wn = wave & 3, g = lane >> 4, jl = lane & 15;
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-        const int n = wn * WAVE_N + 32 * nt + jl;
+        const int n = wn * WAVE_N + 16 * nt + jl;
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-            for (int v4 = 0; v4 < 4; ++v4) {
-                u32x2 p;
-                p[0] = pack_bf16(acc[mt][nt][4 * v4 + 0], acc[mt][nt][4 * v4 + 1]);
-                p[1] = pack_bf16(acc[mt][nt][4 * v4 + 2], acc[mt][nt][4 * v4 + 3]);
-                *reinterpret_cast<u32x2*>(lds + out_tile_offset(n, wm * WAVE_M + 32 * mt + 8 * v4 + 4 * h)) = p;
-            }
+        for (int mt = 0; mt < MT; ++mt) {
+            u32x2 p;
+            p[0] = pack_bf16(acc[mt][nt][0], acc[mt][nt][1]);
+            p[1] = pack_bf16(acc[mt][nt][2], acc[mt][nt][3]);
+            *reinterpret_cast<u32x2*>(lds + out_tile_offset(n, wm * WAVE_M + 16 * mt + 4 * g)) = p;
+        }
     }
 }
 

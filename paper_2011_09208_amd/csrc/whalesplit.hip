@@ -25,7 +25,7 @@ namespace ws {
 constexpr float NEG_INF = -INFINITY;
 constexpr float LOG2E = 1.4426950408889634f;
 
-__device__ __forceinline__ float xor32(float v) { return __shfl_xor(v, 32, 64); }
+__device__ __forceinline__ float lane_xor(float v, int mask) { return __shfl_xor(v, mask, 64); }
 
 // Merge of two (max, sum-exp) pairs; either may be the empty pair (-inf, 0).
 __device__ __forceinline__ void merge_ms(float& m, float& s, float m2, float s2) {
@@ -36,31 +36,28 @@ __device__ __forceinline__ void merge_ms(float& m, float& s, float m2, float s2)
     m = M;
 }
 
-// Class id (relative to the wave's first class) held in accumulator register v of M-tile mt.
-__device__ __forceinline__ int acc_row(int mt, int v, int h) { return 32 * mt + 8 * (v >> 2) + 4 * h + (v & 3); }
+// Class id (relative to the wave's first class) held in accumulator register v of M-tile mt by the
+// lanes of 16-lane group g.
+__device__ __forceinline__ int acc_row(int mt, int v, int g) { return 16 * mt + 4 * g + v; }
 
 // z = acc + bias, with classes beyond the shard set to -inf.  `c_rel0` = the wave's first class
 // relative to the workgroup's tile, `c_left` = number of valid classes from the wave's first class.
-__device__ __forceinline__ void add_bias_and_mask(f32x16 (&acc)[MT][NT], const float* sbias, bool has_bias,
-                                                  int c_rel0, int c_left, int h) {
+__device__ __forceinline__ void add_bias_and_mask(acc_t& acc, const float* sbias, bool has_bias, int c_rel0,
+                                                  int c_left, int g) {
     if (has_bias) {
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
+        for (int mt = 0; mt < MT; ++mt) {
+            const f32x4 b4 = *reinterpret_cast<const f32x4*>(sbias + c_rel0 + 16 * mt + 4 * g);
 #pragma unroll
-            for (int v4 = 0; v4 < 4; ++v4) {
-                const f32x4 b4 = *reinterpret_cast<const f32x4*>(sbias + c_rel0 + 32 * mt + 8 * v4 + 4 * h);
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-#pragma unroll
-                    for (int nt = 0; nt < NT; ++nt) acc[mt][nt][4 * v4 + e] += b4[e];
-            }
+            for (int nt = 0; nt < NT; ++nt) acc[mt][nt] += b4;
+        }
     }
     if (c_left < WAVE_M) {   // wave-uniform: only the ragged last class tile pays for masking
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-            for (int v = 0; v < 16; ++v)
-                if (acc_row(mt, v, h) >= c_left) {
+            for (int v = 0; v < 4; ++v)
+                if (acc_row(mt, v, g) >= c_left) {
 #pragma unroll
                     for (int nt = 0; nt < NT; ++nt) acc[mt][nt][v] = NEG_INF;
                 }
@@ -79,11 +76,11 @@ struct FcArgs {
 
 // Runs the logits GEMM of one 256-class x 256-row tile and leaves z (bias added, padding = -inf)
 // in acc.  M = classes (A = W_s, KC), N = batch rows (B operand = X, KC), K = D.
-__device__ __forceinline__ void logits_tile(f32x16 (&acc)[MT][NT], const FcArgs& a, int ct, int bt, char* lds,
+__device__ __forceinline__ void logits_tile(acc_t& acc, const FcArgs& a, int ct, int bt, char* lds,
                                             float* sbias) {
     zero_acc(acc);
-    Operand A{a.W, a.ldw, a.C - 1, 0};
-    Operand Bo{a.X, a.ldx, a.B - 1, 0};
+    const Operand A = make_operand(a.W, a.ldw, a.C, a.D);
+    const Operand Bo = make_operand(a.X, a.ldx, a.B, a.D);
     gemm_mainloop<KC, KC>(acc, A, Bo, ct * TILE_M, bt * TILE_N, 0, a.D / TILE_K, lds);
     const int tid = threadIdx.x;
     const bool has_bias = a.bias != nullptr;
@@ -95,7 +92,7 @@ __device__ __forceinline__ void logits_tile(f32x16 (&acc)[MT][NT], const FcArgs&
         __syncthreads();
     }
     const int wm = (tid >> 6) >> 2;
-    add_bias_and_mask(acc, sbias, has_bias, wm * WAVE_M, a.C - (ct * TILE_M + wm * WAVE_M), (tid & 63) >> 5);
+    add_bias_and_mask(acc, sbias, has_bias, wm * WAVE_M, a.C - (ct * TILE_M + wm * WAVE_M), (tid & 63) >> 4);
 }
 
 __global__ __launch_bounds__(NTHREADS) void fwd_logits_stats(FcArgs a, float* __restrict__ part_max,
@@ -109,32 +106,35 @@ __global__ __launch_bounds__(NTHREADS) void fwd_logits_stats(FcArgs a, float* __
     if (tile < 0) return;
     const int ct = tile / a.nBT, bt = tile % a.nBT;   // batch tiles fastest: neighbours share the W panel
 
-    f32x16 acc[MT][NT];
+    acc_t acc;
     logits_tile(acc, a, ct, bt, lds, sbias);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 2, wn = wave & 3, h = lane >> 5, jl = lane & 31;
+    const int wm = wave >> 2, wn = wave & 3, g = lane >> 4, jl = lane & 15;
     const int cw0 = ct * TILE_M + wm * WAVE_M;           // first class of this wave (shard-local)
 
+    // A lane holds, for each of its four rows (one per N tile), 32 of the wave's 128 classes; the other
+    // three 16-lane groups hold the rest.
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-        const int row = bt * TILE_N + wn * WAVE_N + 32 * nt + jl;
+        const int row = bt * TILE_N + wn * WAVE_N + 16 * nt + jl;
         float mx = NEG_INF;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) mx = fmaxf(mx, acc[mt][nt][v]);
+            for (int v = 0; v < 4; ++v) mx = fmaxf(mx, acc[mt][nt][v]);
         const float ms = (mx == NEG_INF) ? 0.0f : mx;
         const float shift = -ms * LOG2E;                 // exp(z - m) = exp2(z * log2 e - m * log2 e)
         float s = 0.0f;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) s += __builtin_amdgcn_exp2f(fmaf(acc[mt][nt][v], LOG2E, shift));
-        merge_ms(mx, s, xor32(mx), xor32(s));            // the other half-wave holds the other classes of this row
-        if (h == 0) {
-            red_m[wm * 256 + wn * WAVE_N + 32 * nt + jl] = mx;
-            red_s[wm * 256 + wn * WAVE_N + 32 * nt + jl] = s;
+            for (int v = 0; v < 4; ++v) s += __builtin_amdgcn_exp2f(fmaf(acc[mt][nt][v], LOG2E, shift));
+        merge_ms(mx, s, lane_xor(mx, 16), lane_xor(s, 16));
+        merge_ms(mx, s, lane_xor(mx, 32), lane_xor(s, 32));
+        if (g == 0) {
+            red_m[wm * 256 + wn * WAVE_N + 16 * nt + jl] = mx;
+            red_s[wm * 256 + wn * WAVE_N + 16 * nt + jl] = s;
         }
 
         // Label logit.  Exactly one lane of the whole grid holds z[row][label - offset] when the label
@@ -143,17 +143,17 @@ __global__ __launch_bounds__(NTHREADS) void fwd_logits_stats(FcArgs a, float* __
         const int local = row_ok ? a.labels[row] - a.class_offset : -1;
         const bool in_shard = local >= 0 && local < a.C;
         const int rel = local - cw0;
-        const bool mine = in_shard && rel >= 0 && rel < WAVE_M && (((rel & 31) >> 2) & 1) == h;
+        const bool mine = in_shard && rel >= 0 && rel < WAVE_M && ((rel & 15) >> 2) == g;
         if (__any(mine)) {
             float t = 0.0f;
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    if (acc_row(mt, v, h) == rel) t = acc[mt][nt][v];
+                for (int v = 0; v < 4; ++v)
+                    if (acc_row(mt, v, g) == rel) t = acc[mt][nt][v];
             if (mine) label_logit[row] = t;
         }
-        if (ct == 0 && wm == 0 && h == 0 && row_ok && !in_shard) label_logit[row] = 0.0f;
+        if (ct == 0 && wm == 0 && g == 0 && row_ok && !in_shard) label_logit[row] = 0.0f;
     }
     __syncthreads();
     if (tid < 256) {
@@ -230,43 +230,41 @@ __global__ __launch_bounds__(NTHREADS) void bwd_recompute_dz(FcArgs a, const flo
     if (tile < 0) return;
     const int ct = tile / a.nBT, bt = tile % a.nBT;
 
-    f32x16 acc[MT][NT];
+    acc_t acc;
     logits_tile(acc, a, ct, bt, lds, sbias);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 2, wn = wave & 3, h = lane >> 5, jl = lane & 31;
+    const int wm = wave >> 2, wn = wave & 3, g = lane >> 4, jl = lane & 15;
     const int cw0 = ct * TILE_M + wm * WAVE_M;
 
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-        const int row = bt * TILE_N + wn * WAVE_N + 32 * nt + jl;     // < Bpad: dZ has that many rows
+        const int row = bt * TILE_N + wn * WAVE_N + 16 * nt + jl;     // < Bpad: dZ has that many rows
         const bool row_ok = row < a.B;
         const float lse = row_ok ? logsumexp[row] : 0.0f;
-        const float g = row_ok ? grad_scale : 0.0f;                    // padded rows store exact zeros
+        const float gs = row_ok ? grad_scale : 0.0f;                   // padded rows store exact zeros
         // |g| * exp(z - lse) = exp2(z * log2 e + (log2 |g| - lse * log2 e)): one FMA and one exp2 per
         // element; g = 0 gives a shift of -inf and exact zeros, as does z = -inf on padded classes.
-        const float shift = __log2f(fabsf(g)) - lse * LOG2E;
+        const float shift = __log2f(fabsf(gs)) - lse * LOG2E;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[mt][nt][v] = __builtin_amdgcn_exp2f(fmaf(acc[mt][nt][v], LOG2E, shift));
+            for (int v = 0; v < 4; ++v) acc[mt][nt][v] = __builtin_amdgcn_exp2f(fmaf(acc[mt][nt][v], LOG2E, shift));
         if (grad_scale < 0.0f) {                                        // uniform; the usual scales are positive
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[mt][nt][v] = -acc[mt][nt][v];
+            for (int mt = 0; mt < MT; ++mt) acc[mt][nt] = -acc[mt][nt];
         }
 
         const int local = row_ok ? a.labels[row] - a.class_offset : -1;
         const bool in_shard = local >= 0 && local < a.C;
         const int rel = local - cw0;
-        const bool mine = in_shard && rel >= 0 && rel < WAVE_M && (((rel & 31) >> 2) & 1) == h;
+        const bool mine = in_shard && rel >= 0 && rel < WAVE_M && ((rel & 15) >> 2) == g;
         if (__any(mine)) {
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    if (mine && acc_row(mt, v, h) == rel) acc[mt][nt][v] -= g;
+                for (int v = 0; v < 4; ++v)
+                    if (mine && acc_row(mt, v, g) == rel) acc[mt][nt][v] -= gs;
         }
     }
 
@@ -308,7 +306,8 @@ struct DxArgs {
     float* out; int64_t ldo; int64_t split_stride;   // out[split][b][d]
 };
 
-// dX^T tile: M = features d (A = W_s read k-strided), N = batch rows (B operand = dz, k contiguous),
+// dX tile: M = batch rows (A = dz, k contiguous), N = features d (B operand = W_s read k-strided: the
+// narrower side of a wave's sub-tile, so the slower transposing LDS reads are the fewer ones),
 // K = the shard's classes, cut into `splits` ranges.
 __global__ __launch_bounds__(NTHREADS) void bwd_dx(DxArgs a) {
     __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
@@ -321,29 +320,25 @@ __global__ __launch_bounds__(NTHREADS) void bwd_dx(DxArgs a) {
     int ns = a.steps_total - s0;
     ns = ns < a.steps_per_split ? ns : a.steps_per_split;
 
-    f32x16 acc[MT][NT];
+    acc_t acc;
     zero_acc(acc);
-    Operand A{a.W, a.ldw, a.C - 1, a.D - 8};
-    Operand Bo{a.dZ, a.ldz, a.Bpad - 1, 0};
-    gemm_mainloop<KS, KC>(acc, A, Bo, dt * TILE_M, bt * TILE_N, s0 * TILE_K, ns, lds);
+    const Operand A = make_operand(a.dZ, a.ldz, a.Bpad, a.ldz);
+    const Operand Bo = make_operand(a.W, a.ldw, a.C, a.D);          // classes beyond the shard read as zeros
+    gemm_mainloop<KC, KS>(acc, A, Bo, bt * TILE_M, dt * TILE_N, s0 * TILE_K, ns, lds);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 2, wn = wave & 3, h = lane >> 5, jl = lane & 31;
+    const int wm = wave >> 2, wn = wave & 3, g = lane >> 4, jl = lane & 15;
     float* out = a.out + sp * a.split_stride;
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-        const int row = bt * TILE_N + wn * WAVE_N + 32 * nt + jl;
-        if (row >= a.B) continue;
+        const int d = dt * TILE_N + wn * WAVE_N + 16 * nt + jl;
+        if (d >= a.D) continue;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-            for (int v4 = 0; v4 < 4; ++v4) {
-                const int d = dt * TILE_M + wm * WAVE_M + 32 * mt + 8 * v4 + 4 * h;
-                if (d < a.D) {
-                    f32x4 o = {acc[mt][nt][4 * v4], acc[mt][nt][4 * v4 + 1], acc[mt][nt][4 * v4 + 2],
-                               acc[mt][nt][4 * v4 + 3]};
-                    *reinterpret_cast<f32x4*>(out + (int64_t)row * a.ldo + d) = o;
-                }
+            for (int v = 0; v < 4; ++v) {
+                const int row = bt * TILE_M + wm * WAVE_M + 16 * mt + 4 * g + v;
+                if (row < a.B) out[(int64_t)row * a.ldo + d] = acc[mt][nt][v];
             }
     }
 }
@@ -383,7 +378,7 @@ __global__ __launch_bounds__(256) void finish_bwd(const float* __restrict__ part
 struct DwArgs {
     const uint16_t* XT; int64_t ldxt;    // [D][Bpad]
     const uint16_t* dZT; int64_t ldzt;   // [Cpad][Bpad]
-    int D, C;
+    int D, C, Cpad;
     int nDT, nCT, k_steps;
     uint16_t* dW; int64_t lddw;
 };
@@ -396,10 +391,10 @@ __global__ __launch_bounds__(NTHREADS) void bwd_dw(DwArgs a) {
     if (tile < 0) return;
     const int dt = tile % a.nDT, ct = tile / a.nDT;    // feature tiles fastest: neighbours share the dz panel
 
-    f32x16 acc[MT][NT];
+    acc_t acc;
     zero_acc(acc);
-    Operand A{a.XT, a.ldxt, a.D - 1, 0};
-    Operand Bo{a.dZT, a.ldzt, INT_MAX, 0};             // dz^T is padded to whole tiles: never clamped
+    const Operand A = make_operand(a.XT, a.ldxt, a.D, a.ldxt);
+    const Operand Bo = make_operand(a.dZT, a.ldzt, a.Cpad, a.ldzt);
     gemm_mainloop<KC, KC>(acc, A, Bo, dt * TILE_M, ct * TILE_N, 0, a.k_steps, lds);
 
     // [class][feature] tile through LDS, then whole 512-byte rows of dW
@@ -424,6 +419,9 @@ struct BwdPlan {
 };
 
 static bool shape_ok(int32_t B, int32_t D, int32_t C) { return B > 0 && D > 0 && C > 0 && D % 64 == 0; }
+
+// The kernels address an operand with 32-bit byte offsets, tiles may hang 256 rows over its end.
+static bool fits_32bit_offsets(int64_t rows, int64_t ld) { return (rows + 256) * ld * 2 < ((int64_t)1 << 32); }
 
 static BwdPlan plan_bwd(int32_t B, int32_t D, int32_t C) {
     BwdPlan p;
@@ -454,6 +452,7 @@ static int check_fc_common(const void* X, int64_t ldx, const void* W, int64_t ld
     if (!X || !W || !labels) return WS_ERR_NULL;
     if (!shape_ok(B, D, C)) return WS_ERR_SHAPE;
     if (ldx < D || ldw < D) return WS_ERR_SHAPE;
+    if (!fits_32bit_offsets(B, ldx) || !fits_32bit_offsets(C, ldw)) return WS_ERR_SHAPE;
     if (class_offset < 0 || (int64_t)class_offset + C > INT32_MAX) return WS_ERR_RANGE;
     if (!aligned(X, 16) || !aligned(W, 16) || ldx % 8 || ldw % 8) return WS_ERR_ALIGN;
     if (!aligned(labels, 4) || (bias && !aligned(bias, 4))) return WS_ERR_ALIGN;
@@ -588,6 +587,8 @@ int ws_split_fc_bwd(const void* X, int64_t ldx, const void* W_shard, int64_t ldw
     if (!aligned(dX_partial, 16) || !aligned(dW_shard, 16) || lddx % 4 || lddw % 8) return WS_ERR_ALIGN;
     if (!aligned(logsumexp, 4) || (db_shard && !aligned(db_shard, 4))) return WS_ERR_ALIGN;
     const BwdPlan p = plan_bwd(B, D, C_shard);
+    if (!fits_32bit_offsets(p.Bpad, p.Cpad) || !fits_32bit_offsets(p.Cpad, p.Bpad) || !fits_32bit_offsets(D, p.Bpad))
+        return WS_ERR_SHAPE;
     if (!workspace || workspace_bytes < 2 * p.dz_bytes + p.xt_bytes + p.dbp_bytes + p.parts_bytes) return WS_ERR_WORKSPACE;
     if (!aligned(workspace, 16)) return WS_ERR_ALIGN;
 
@@ -631,7 +632,7 @@ int ws_split_fc_bwd(const void* X, int64_t ldx, const void* W_shard, int64_t ldw
 
     DwArgs w;
     w.XT = XT; w.ldxt = p.Bpad; w.dZT = dZT; w.ldzt = p.Bpad;
-    w.D = D; w.C = C_shard;
+    w.D = D; w.C = C_shard; w.Cpad = (int)p.Cpad;
     w.nDT = p.nDT; w.nCT = p.nCT; w.k_steps = (B + TILE_K - 1) / TILE_K;
     w.dW = static_cast<uint16_t*>(dW_shard); w.lddw = lddw;
     WS_LAUNCH(KID_DW, bwd_dw, dim3(xcd_grid(p.nDT * p.nCT)), dim3(NTHREADS), s, w);
