@@ -111,7 +111,7 @@ def main():
     plain_ms = (time.perf_counter() - t0) * 1e3 / args.steps
 
     # the timed region proper: every kernel launch bracketed by HIP events on its stream
-    ws.profile_enable(args.steps * (9 * S + 2) + 16)
+    ws.profile_enable(args.steps * (7 * S + 2) + 16)
     ws.profile_reset()
     torch.cuda.synchronize()
     t0 = time.perf_counter()

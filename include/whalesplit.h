@@ -111,7 +111,7 @@ size_t ws_bwd_workspace_bytes(int32_t B, int32_t D, int32_t C_shard);
  *   dz[i][c]   = grad_scale * (exp(z[i][c] - logsumexp[i]) - [labels[i] == class_offset + c])
  *   dX_partial = dz . W_shard      fp32 [B][lddx]  (overwritten, or += if accumulate_dx != 0)
  *   dW_shard   = dz^T . X          bf16 [C_shard][lddw]
- *   db_shard   = column sums of dz fp32 [C_shard]   (skipped if NULL)
+ *   db_shard   = column sums of dz fp32 [C_shard]   (skipped if NULL; summed before dz is rounded)
  * dz is held once, in bf16, in the workspace.  grad_scale = 1 gives the gradient of
  * the summed loss, 1/B that of the mean loss.  dX_partial is this shard's share of
  * the feature gradient: the sum over shards is the full dX (what flows back over

@@ -338,9 +338,8 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 // makes direct global stores 8 or 16 bytes wide and scattered over 16 rows.  Instead the 256 x 256 tile
 // is rounded to bf16 and laid out in LDS as [n][m] (512 bytes per n; it fills the 128 KiB the main loop
 // no longer needs), then written out row by row.  Eight-byte slots are XOR-swizzled by a bit permutation
-// of n chosen so that all three access patterns spread over the banks: the accumulator writes (32
-// consecutive n, one slot), the transposing reads (4 consecutive n x 4 consecutive slots per 16 lanes,
-// n 8 apart between the lane blocks) and the row reads (one n, all slots).
+// of n chosen so that both access patterns spread over the banks: the accumulator writes (16
+// consecutive n x 4 slots that are 4 apart per wave instruction) and the row reads (one n, all slots).
 
 __device__ __forceinline__ int out_tile_swizzle(int n) {
     return ((n >> 2) & 1) | (((n >> 4) & 1) << 1) | ((n & 1) << 2) | (((n >> 1) & 1) << 3) | (((n >> 3) & 1) << 4);
@@ -384,40 +383,6 @@ __device__ __forceinline__ void lds_tile_store_rows(const char* lds, uint16_t* o
             if (g & 1) v = __builtin_shufflevector(v, v, 2, 3, 0, 1);
             __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(out + (int64_t)n * ld + cq * 8));
         }
-    }
-}
-
-// Writes the LDS tile transposed, out[m][n] (`out` = address of element (m = 0, n = 0)), all 256 x 256
-// elements (the destination is padded to whole tiles), and returns in lanes 0..15 of each wave the
-// sums over all 256 n of columns m = 32 * wave + 16 * u + lane, u = 0, 1 (as rounded to bf16).
-// The transpose uses ds_read_b64_tr_b16: a block of 16 lanes reads 4 n-rows x 16 m-columns and
-// each lane receives the 4 n of one m.
-__device__ __forceinline__ void lds_tile_store_transposed(const char* lds, uint16_t* out, int64_t ld,
-                                                          float (&colsum)[2]) {
-    typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int blk = lane >> 4, i = lane & 15;
-    const int e = i >> 2;               // which of the four n-rows this lane addresses
-    const int mc = 4 * (i & 3);         // first of the four m-columns this lane addresses
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-        const int m0 = 32 * wave + 16 * u;
-        float sum = 0.0f;
-#pragma unroll 2
-        for (int it = 0; it < 8; ++it) {
-            const int n0 = 32 * it + 8 * blk;            // this block of lanes covers n0 .. n0 + 7
-            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (lds_s16x4_ptr)(lds + out_tile_offset(n0 + e, m0 + mc)));
-            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (lds_s16x4_ptr)(lds + out_tile_offset(n0 + 4 + e, m0 + mc)));
-            const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-#pragma unroll
-            for (int k = 0; k < 8; ++k) sum += __uint_as_float(((uint32_t)(uint16_t)v[k]) << 16);
-            *reinterpret_cast<s16x8*>(out + (int64_t)(m0 + i) * ld + n0) = v;
-        }
-        sum += __shfl_xor(sum, 16, 64);
-        sum += __shfl_xor(sum, 32, 64);
-        colsum[u] = sum;
     }
 }
 

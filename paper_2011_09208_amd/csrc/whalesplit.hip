@@ -5,14 +5,14 @@
 //                      logit reduced in the epilogue; one (max, sum) partial per 256-class tile
 //   merge_class_tiles  merges those partials into row_max / row_sumexp of the shard
 //   combine_partials   merges the shards' statistics into logsumexp and loss
-//   transpose_x        X^T for the dW contraction
-//   bwd_recompute_dz   same GEMM again, epilogue dz = g (exp(z - lse) - onehot) stored as bf16, both
-//                      row-major and transposed; column sums of the tile (db partials)
+//   bwd_recompute_dz   same GEMM again, epilogue dz = g (exp(z - lse) - onehot) stored as bf16
+//                      [row][class]; column sums of the tile (db partials); its surplus workgroups
+//                      write X^T for the dW contraction
 //   bwd_dx             dX_partial = dz . W_s, split along the class contraction; partial sums
-//   finish_bwd         sums the split-K partials of dX (optionally accumulating into the caller's dX)
-//                      and the db partials
-//   bwd_dw             dW_s = dz^T . X
+//   bwd_dw             dW_s = dz^T . X; its surplus workgroups sum the split-K partials of dX
+//                      (optionally accumulating into the caller's dX) and the db partials
 #include <hip/hip_runtime.h>
+#include <algorithm>
 #include <limits.h>
 #include <math.h>
 #include <stdint.h>
@@ -165,23 +165,36 @@ __global__ __launch_bounds__(NTHREADS) void fwd_logits_stats(FcArgs a, float* __
     }
 }
 
-// One workgroup merges the class-tile partials of 64 rows: thread (r, q) folds tiles q, q + 16, ...
-// of row r online, then the 16 partial pairs of a row are merged through LDS in a fixed order.
+// One workgroup merges the class-tile partials of 16 rows: thread (r, q) folds tiles q, q + 64, ...
+// of row r online, then the 64 partial pairs of a row are merged through LDS in a fixed order
+// (8 groups of 8, then the 8 group results).
 __global__ __launch_bounds__(1024) void merge_class_tiles(const float* __restrict__ part_max,
                                                            const float* __restrict__ part_sum, int nCT, int Bpad,
                                                            int B, float* __restrict__ row_max,
                                                            float* __restrict__ row_sumexp) {
-    __shared__ float sm[16][64], ss[16][64];
-    const int r = threadIdx.x & 63, q = threadIdx.x >> 6;
-    const int i = blockIdx.x * 64 + r;          // < Bpad: the partial arrays are padded to whole tiles
+    __shared__ float sm[64][16], ss[64][16];
+    const int r = threadIdx.x & 15, q = threadIdx.x >> 4;
+    const int i = blockIdx.x * 16 + r;          // < Bpad: the partial arrays are padded to whole tiles
     float m = NEG_INF, s = 0.0f;
-    for (int t = q; t < nCT; t += 16) merge_ms(m, s, part_max[(int64_t)t * Bpad + i], part_sum[(int64_t)t * Bpad + i]);
+    for (int t = q; t < nCT; t += 64) merge_ms(m, s, part_max[(int64_t)t * Bpad + i], part_sum[(int64_t)t * Bpad + i]);
     sm[q][r] = m;
     ss[q][r] = s;
     __syncthreads();
+    if (q < 8) {
+        m = sm[8 * q][r];
+        s = ss[8 * q][r];
+#pragma unroll
+        for (int k = 1; k < 8; ++k) merge_ms(m, s, sm[8 * q + k][r], ss[8 * q + k][r]);
+    }
+    __syncthreads();
+    if (q < 8) {
+        sm[q][r] = m;
+        ss[q][r] = s;
+    }
+    __syncthreads();
     if (q == 0 && i < B) {
 #pragma unroll
-        for (int k = 1; k < 16; ++k) merge_ms(m, s, sm[k][r], ss[k][r]);
+        for (int k = 1; k < 8; ++k) merge_ms(m, s, sm[k][r], ss[k][r]);
         row_max[i] = m;
         row_sumexp[i] = s;
     }
@@ -220,12 +233,38 @@ __global__ __launch_bounds__(1024) void mean_loss_kernel(const float* __restrict
     if (threadIdx.x == 0) *loss_mean = red[0] / (float)B;
 }
 
+// XT[d][b] = X[b][d], zero for b >= B (the dW contraction reads whole 64-row k-steps), in 64 x 64
+// tiles through LDS.  Run by the workgroups of bwd_recompute_dz beyond its GEMM tiles: they are handed
+// out last, onto compute units the final, partial round of GEMM tiles leaves idle.
+struct XtArgs {
+    uint16_t* XT; int64_t ldxt;          // [D][Bpad]
+    int first_block, n_blocks;           // workgroups [first_block, first_block + n_blocks) transpose
+};
+
+__device__ __forceinline__ void transpose_x_tiles(const FcArgs& a, const XtArgs& x, int worker, char* lds) {
+    uint16_t (*tile)[66] = reinterpret_cast<uint16_t (*)[66]>(lds);
+    const int nb = a.Bpad / 64, n_tiles = nb * (a.D / 64);
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int t = worker; t < n_tiles; t += x.n_blocks) {
+        const int b0 = (t % nb) * 64, d0 = (t / nb) * 64;
+        for (int r = ty; r < 64; r += NTHREADS / 64)
+            tile[r][tx] = (b0 + r < a.B) ? a.X[(int64_t)(b0 + r) * a.ldx + d0 + tx] : (uint16_t)0;
+        __syncthreads();
+        for (int r = ty; r < 64; r += NTHREADS / 64) x.XT[(int64_t)(d0 + r) * x.ldxt + b0 + tx] = tile[tx][r];
+        __syncthreads();
+    }
+}
+
 __global__ __launch_bounds__(NTHREADS) void bwd_recompute_dz(FcArgs a, const float* __restrict__ logsumexp,
                                                               float grad_scale, uint16_t* __restrict__ dZ,
-                                                              int64_t ldz, uint16_t* __restrict__ dZT,
-                                                              int64_t ldzt, float* __restrict__ db_part) {
+                                                              int64_t ldz, float* __restrict__ db_part,
+                                                              XtArgs xt) {
     __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
     float* sbias = reinterpret_cast<float*>(lds);
+    if ((int)blockIdx.x >= xt.first_block) {
+        transpose_x_tiles(a, xt, (int)blockIdx.x - xt.first_block, lds);
+        return;
+    }
     const int tile = xcd_logical_tile(a.nBT * a.nCT);
     if (tile < 0) return;
     const int ct = tile / a.nBT, bt = tile % a.nBT;
@@ -268,33 +307,41 @@ __global__ __launch_bounds__(NTHREADS) void bwd_recompute_dz(FcArgs a, const flo
         }
     }
 
-    // dz goes out twice: [row][class] feeds the dX contraction (over classes) and [class][row] the dW
-    // contraction (over rows), so both read it contiguous along their contraction index.  The tile is
-    // staged in LDS so that both copies leave in whole rows; the transposed pass also yields the
-    // tile's column sums, this row tile's share of db.
+    // db: the tile's column sums over its batch rows, taken from the fp32 values.  A lane first adds
+    // its four N-tiles, then the 16 lanes that hold the same classes reduce-scatter their 32 sums in
+    // four exchange steps (16, 8, 4, 2 values sent), which leaves lane jl the sums of accumulator
+    // rows 2 jl and 2 jl + 1 (row index = 4 * M-tile + register).  One partial per wave column:
+    // db_part[4 * bt + wn][class].
+    if (db_part != nullptr) {
+        float val[4 * MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                val[4 * mt + v] = (acc[mt][0][v] + acc[mt][1][v]) + (acc[mt][2][v] + acc[mt][3][v]);
+#pragma unroll
+        for (int step = 0; step < 4; ++step) {
+            const int h = (2 * MT) >> step, mask = 8 >> step;
+            const bool up = (jl & mask) != 0;
+#pragma unroll
+            for (int i = 0; i < h; ++i) {
+                const float keep = up ? val[i + h] : val[i];
+                const float send = up ? val[i] : val[i + h];
+                val[i] = keep + lane_xor(send, mask);
+            }
+        }
+        const int cls = cw0 + 16 * (jl >> 1) + 4 * g + 2 * (jl & 1);
+        f32x2 two = {val[0], val[1]};
+        *reinterpret_cast<f32x2*>(db_part + (int64_t)(4 * bt + wn) * ldz + cls) = two;
+    }
+
+    // dz [row][class] feeds both the dX contraction (over classes, read along its rows) and the dW
+    // contraction (over rows, read across them).  The tile is staged in LDS so that it leaves in
+    // whole 512-byte rows.
     __syncthreads();                       // the bias staging area is about to be overwritten
     acc_to_lds_bf16(acc, lds);
     __syncthreads();
     lds_tile_store_rows(lds, dZ + (int64_t)bt * TILE_N * ldz + ct * TILE_M, ldz, TILE_N, TILE_M);
-    float colsum[2];
-    lds_tile_store_transposed(lds, dZT + (int64_t)ct * TILE_M * ldzt + bt * TILE_N, ldzt, colsum);
-    if (db_part != nullptr && lane < 16) {
-        float* o = db_part + (int64_t)bt * ldz + ct * TILE_M + 32 * wave + lane;
-        o[0] = colsum[0];
-        o[16] = colsum[1];
-    }
-}
-
-// XT[d][b] = X[b][d], zero for b >= B (the dW contraction reads whole 64-row k-steps).
-// 64 x 64 tiles through LDS; grid (Bpad / 64, D / 64), 256 threads.
-__global__ __launch_bounds__(256) void transpose_x(const uint16_t* __restrict__ X, int64_t ldx, int B,
-                                                    uint16_t* __restrict__ XT, int64_t ldxt) {
-    __shared__ uint16_t tile[64][66];
-    const int b0 = blockIdx.x * 64, d0 = blockIdx.y * 64;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    for (int r = ty; r < 64; r += 4) tile[r][tx] = (b0 + r < B) ? X[(int64_t)(b0 + r) * ldx + d0 + tx] : (uint16_t)0;
-    __syncthreads();
-    for (int r = ty; r < 64; r += 4) XT[(int64_t)(d0 + r) * ldxt + b0 + tx] = tile[tx][r];
 }
 
 struct DxArgs {
@@ -343,50 +390,65 @@ __global__ __launch_bounds__(NTHREADS) void bwd_dx(DxArgs a) {
     }
 }
 
-// Finishes the two small reductions of the backward call in one launch: workgroups [0, dx_blocks) sum
-// the split-K partials of dX in a fixed order (one float4 per thread; optionally accumulating into the
-// caller's dX), the remaining workgroups sum the per-row-tile column sums into db.
-__global__ __launch_bounds__(256) void finish_bwd(const float* __restrict__ parts, int splits, int64_t split_stride,
-                                                   int B, int D, float* __restrict__ dX, int64_t lddx, int accumulate,
-                                                   int dx_blocks, const float* __restrict__ db_part, int nBT,
-                                                   int64_t db_stride, int C, float* __restrict__ db) {
-    if ((int)blockIdx.x < dx_blocks) {
-        const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-        const int d4 = D >> 2;
-        if (i >= (int64_t)B * d4) return;
-        const int row = (int)(i / d4), d = (int)(i % d4) * 4;
-        f32x4 s = {0.f, 0.f, 0.f, 0.f};
-        for (int p = 0; p < splits; ++p)
-            s += *reinterpret_cast<const f32x4*>(parts + p * split_stride + (int64_t)row * D + d);
-        float* o = dX + (int64_t)row * lddx + d;
-        if (accumulate) {
+// The two small reductions that finish the backward call: the split-K partials of dX are summed in a
+// fixed order (one float4 per thread and turn; optionally accumulating into the caller's dX), and the
+// per-row-tile column sums into db.  Run by the workgroups of bwd_dw beyond its GEMM tiles (handed out
+// last, onto compute units that the final, partial round of GEMM tiles leaves idle).
+struct FinishArgs {
+    const float* parts; int splits; int64_t split_stride;   // nullptr: dX was written directly
+    int B, D;
+    float* dX; int64_t lddx; int accumulate;
+    const float* db_part; int n_db_parts; int64_t db_stride; // nullptr: no db wanted
+    int C; float* db;
+    int first_block, n_blocks;
+};
+
+__device__ __forceinline__ void finish_bwd(const FinishArgs& f, int worker) {
+    const int64_t stride = (int64_t)f.n_blocks * NTHREADS;
+    const int64_t me = (int64_t)worker * NTHREADS + threadIdx.x;
+    if (f.parts != nullptr) {
+        const int d4 = f.D >> 2;
+        const int64_t n4 = (int64_t)f.B * d4;
+        for (int64_t i = me; i < n4; i += stride) {
+            const int row = (int)(i / d4), d = (int)(i % d4) * 4;
+            f32x4 s = {0.f, 0.f, 0.f, 0.f};
+            for (int p = 0; p < f.splits; ++p)
+                s += *reinterpret_cast<const f32x4*>(f.parts + p * f.split_stride + (int64_t)row * f.D + d);
+            float* o = f.dX + (int64_t)row * f.lddx + d;
+            if (f.accumulate) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) o[e] += s[e];
-        } else {
+                for (int e = 0; e < 4; ++e) o[e] += s[e];
+            } else {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) o[e] = s[e];
+                for (int e = 0; e < 4; ++e) o[e] = s[e];
+            }
         }
-    } else {
-        const int c = ((int)blockIdx.x - dx_blocks) * blockDim.x + threadIdx.x;
-        if (c >= C) return;
-        float s = 0.0f;
-        for (int t = 0; t < nBT; ++t) s += db_part[t * db_stride + c];
-        db[c] = s;
+    }
+    if (f.db_part != nullptr) {
+        for (int64_t c = me; c < f.C; c += stride) {
+            float s = 0.0f;
+            for (int t = 0; t < f.n_db_parts; ++t) s += f.db_part[t * f.db_stride + c];
+            f.db[c] = s;
+        }
     }
 }
 
 struct DwArgs {
     const uint16_t* XT; int64_t ldxt;    // [D][Bpad]
-    const uint16_t* dZT; int64_t ldzt;   // [Cpad][Bpad]
-    int D, C, Cpad;
+    const uint16_t* dZ; int64_t ldz;     // [Bpad][Cpad]
+    int D, C, Bpad;
     int nDT, nCT, k_steps;
     uint16_t* dW; int64_t lddw;
 };
 
-// dW^T tile: M = features d (A = X^T), N = classes (B operand = dz^T), K = batch rows; both operands
-// are contiguous along the rows.
-__global__ __launch_bounds__(NTHREADS) void bwd_dw(DwArgs a) {
+// dW^T tile: M = features d (A = X^T, k contiguous), N = classes (B operand = dz read k-strided, the
+// narrower side of a wave's sub-tile as in bwd_dx), K = batch rows.
+__global__ __launch_bounds__(NTHREADS) void bwd_dw(DwArgs a, FinishArgs fin) {
     __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
+    if ((int)blockIdx.x >= fin.first_block) {
+        finish_bwd(fin, (int)blockIdx.x - fin.first_block);
+        return;
+    }
     const int tile = xcd_logical_tile(a.nDT * a.nCT);
     if (tile < 0) return;
     const int dt = tile % a.nDT, ct = tile / a.nDT;    // feature tiles fastest: neighbours share the dz panel
@@ -394,8 +456,8 @@ __global__ __launch_bounds__(NTHREADS) void bwd_dw(DwArgs a) {
     acc_t acc;
     zero_acc(acc);
     const Operand A = make_operand(a.XT, a.ldxt, a.D, a.ldxt);
-    const Operand Bo = make_operand(a.dZT, a.ldzt, a.Cpad, a.ldzt);
-    gemm_mainloop<KC, KC>(acc, A, Bo, dt * TILE_M, ct * TILE_N, 0, a.k_steps, lds);
+    const Operand Bo = make_operand(a.dZ, a.ldz, a.Bpad, a.ldz);
+    gemm_mainloop<KC, KS>(acc, A, Bo, dt * TILE_M, ct * TILE_N, 0, a.k_steps, lds);
 
     // [class][feature] tile through LDS, then whole 512-byte rows of dW
     acc_to_lds_bf16(acc, lds);
@@ -410,12 +472,14 @@ __global__ __launch_bounds__(NTHREADS) void bwd_dw(DwArgs a) {
 static inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 static inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 static inline int xcd_grid(int n_tiles) { return 8 * ((n_tiles + 7) / 8); }
+// Workgroups appended to a GEMM launch for its small side job (X^T, the final reductions).
+static const int SIDE_BLOCKS = 128;
 
 struct BwdPlan {
     int64_t Bpad, Cpad;
     int nBT, nCT, nDT;
     int steps_total, splits, steps_per_split;
-    size_t dz_bytes, xt_bytes, dbp_bytes, parts_bytes;     // dz and dz^T take dz_bytes each
+    size_t dz_bytes, xt_bytes, dbp_bytes, parts_bytes;
 };
 
 static bool shape_ok(int32_t B, int32_t D, int32_t C) { return B > 0 && D > 0 && C > 0 && D % 64 == 0; }
@@ -438,7 +502,7 @@ static BwdPlan plan_bwd(int32_t B, int32_t D, int32_t C) {
     p.splits = (p.steps_total + p.steps_per_split - 1) / p.steps_per_split;
     p.dz_bytes = (size_t)p.Bpad * p.Cpad * 2;
     p.xt_bytes = (size_t)D * p.Bpad * 2;
-    p.dbp_bytes = (size_t)p.nBT * p.Cpad * 4;
+    p.dbp_bytes = (size_t)4 * p.nBT * p.Cpad * 4;        // one db partial per 64-row wave column
     p.parts_bytes = (size_t)p.splits * B * D * 4;
     return p;
 }
@@ -464,10 +528,9 @@ static int check_fc_common(const void* X, int64_t ldx, const void* W, int64_t ld
 // When enabled, every kernel launch is bracketed by a pair of events recorded on the launch stream.
 // The pairs come from a pool created by ws_profile_enable; when the pool is used up, launches go
 // untimed.  Not thread safe; meant for benchmarks.
-enum KernelId { KID_FWD = 0, KID_MERGE, KID_COMBINE, KID_MEAN, KID_XT, KID_DZ, KID_DX, KID_FINISH, KID_DW, KID_COUNT };
+enum KernelId { KID_FWD = 0, KID_MERGE, KID_COMBINE, KID_MEAN, KID_DZ, KID_DX, KID_DW, KID_COUNT };
 static const char* const kKernelNames[KID_COUNT] = {"fwd_logits_stats", "merge_class_tiles", "combine_partials",
-                                                    "mean_loss", "transpose_x", "bwd_recompute_dz", "bwd_dx",
-                                                    "finish_bwd", "bwd_dw"};
+                                                    "mean_loss", "bwd_recompute_dz", "bwd_dx", "bwd_dw"};
 struct ProfState {
     bool on = false;
     int capacity = 0, used = 0;
@@ -527,7 +590,7 @@ size_t ws_fwd_workspace_bytes(int32_t B, int32_t D, int32_t C_shard) {
 size_t ws_bwd_workspace_bytes(int32_t B, int32_t D, int32_t C_shard) {
     if (!shape_ok(B, D, C_shard)) return 0;
     const BwdPlan p = plan_bwd(B, D, C_shard);
-    return 2 * p.dz_bytes + p.xt_bytes + p.dbp_bytes + p.parts_bytes;
+    return p.dz_bytes + p.xt_bytes + p.dbp_bytes + p.parts_bytes;
 }
 
 int ws_split_fc_fwd(const void* X, int64_t ldx, const void* W_shard, int64_t ldw, const float* b_shard,
@@ -554,7 +617,7 @@ int ws_split_fc_fwd(const void* X, int64_t ldx, const void* W_shard, int64_t ldw
     hipStream_t s = static_cast<hipStream_t>(stream);
     WS_LAUNCH(KID_FWD, fwd_logits_stats, dim3(xcd_grid(a.nBT * a.nCT)), dim3(NTHREADS), s, a, part_max,
                        part_sum, label_logit);
-    WS_LAUNCH(KID_MERGE, merge_class_tiles, dim3((B + 63) / 64), dim3(1024), s, part_max, part_sum, a.nCT,
+    WS_LAUNCH(KID_MERGE, merge_class_tiles, dim3((B + 15) / 16), dim3(1024), s, part_max, part_sum, a.nCT,
                        a.Bpad, B, row_max, row_sumexp);
     return launch_status();
 }
@@ -587,17 +650,16 @@ int ws_split_fc_bwd(const void* X, int64_t ldx, const void* W_shard, int64_t ldw
     if (!aligned(dX_partial, 16) || !aligned(dW_shard, 16) || lddx % 4 || lddw % 8) return WS_ERR_ALIGN;
     if (!aligned(logsumexp, 4) || (db_shard && !aligned(db_shard, 4))) return WS_ERR_ALIGN;
     const BwdPlan p = plan_bwd(B, D, C_shard);
-    if (!fits_32bit_offsets(p.Bpad, p.Cpad) || !fits_32bit_offsets(p.Cpad, p.Bpad) || !fits_32bit_offsets(D, p.Bpad))
+    if (!fits_32bit_offsets(p.Bpad, p.Cpad) || !fits_32bit_offsets(D, p.Bpad))
         return WS_ERR_SHAPE;
-    if (!workspace || workspace_bytes < 2 * p.dz_bytes + p.xt_bytes + p.dbp_bytes + p.parts_bytes) return WS_ERR_WORKSPACE;
+    if (!workspace || workspace_bytes < p.dz_bytes + p.xt_bytes + p.dbp_bytes + p.parts_bytes) return WS_ERR_WORKSPACE;
     if (!aligned(workspace, 16)) return WS_ERR_ALIGN;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     uint16_t* dZ = static_cast<uint16_t*>(workspace);
-    uint16_t* dZT = dZ + (size_t)p.Bpad * p.Cpad;
-    uint16_t* XT = dZT + (size_t)p.Bpad * p.Cpad;
-    float* db_part = reinterpret_cast<float*>(static_cast<char*>(workspace) + 2 * p.dz_bytes + p.xt_bytes);
-    float* parts = db_part + (size_t)p.nBT * p.Cpad;
+    uint16_t* XT = dZ + (size_t)p.Bpad * p.Cpad;
+    float* db_part = reinterpret_cast<float*>(static_cast<char*>(workspace) + p.dz_bytes + p.xt_bytes);
+    float* parts = db_part + (size_t)4 * p.nBT * p.Cpad;
 
     FcArgs a;
     a.X = static_cast<const uint16_t*>(X); a.ldx = ldx;
@@ -605,10 +667,12 @@ int ws_split_fc_bwd(const void* X, int64_t ldx, const void* W_shard, int64_t ldw
     a.bias = b_shard; a.labels = labels;
     a.B = B; a.D = D; a.C = C_shard; a.class_offset = class_offset;
     a.Bpad = (int)p.Bpad; a.nBT = p.nBT; a.nCT = p.nCT;
-    WS_LAUNCH(KID_XT, transpose_x, dim3((unsigned)(p.Bpad / 64), (unsigned)(D / 64)), dim3(256), s, a.X, ldx, B,
-              XT, p.Bpad);
-    WS_LAUNCH(KID_DZ, bwd_recompute_dz, dim3(xcd_grid(p.nBT * p.nCT)), dim3(NTHREADS), s, a, logsumexp,
-              grad_scale, dZ, p.Cpad, dZT, p.Bpad, db_shard ? db_part : nullptr);
+    XtArgs xt;
+    xt.XT = XT; xt.ldxt = p.Bpad;
+    xt.first_block = xcd_grid(p.nBT * p.nCT);
+    xt.n_blocks = (int)std::min<int64_t>((p.Bpad / 64) * (D / 64), SIDE_BLOCKS);
+    WS_LAUNCH(KID_DZ, bwd_recompute_dz, dim3(xt.first_block + xt.n_blocks), dim3(NTHREADS), s, a, logsumexp,
+              grad_scale, dZ, p.Cpad, db_shard ? db_part : nullptr, xt);
 
     DxArgs x;
     x.dZ = dZ; x.ldz = p.Cpad; x.W = a.W; x.ldw = ldw;
@@ -620,22 +684,19 @@ int ws_split_fc_bwd(const void* X, int64_t ldx, const void* W_shard, int64_t ldw
     x.ldo = direct ? lddx : D;
     x.split_stride = (int64_t)B * D;
     WS_LAUNCH(KID_DX, bwd_dx, dim3(xcd_grid(p.nDT * p.nBT * p.splits)), dim3(NTHREADS), s, x);
-    {
-        const int64_t n4 = (int64_t)B * (D / 4);
-        const int dx_blocks = direct ? 0 : (int)((n4 + 255) / 256);
-        const int db_blocks = db_shard ? (C_shard + 255) / 256 : 0;
-        if (dx_blocks + db_blocks > 0)
-            WS_LAUNCH(KID_FINISH, finish_bwd, dim3((unsigned)(dx_blocks + db_blocks)), dim3(256), s, parts, p.splits,
-                      (int64_t)B * D, B, D, dX_partial, lddx, accumulate_dx, dx_blocks, db_part, p.nBT, p.Cpad,
-                      C_shard, db_shard);
-    }
-
     DwArgs w;
-    w.XT = XT; w.ldxt = p.Bpad; w.dZT = dZT; w.ldzt = p.Bpad;
-    w.D = D; w.C = C_shard; w.Cpad = (int)p.Cpad;
+    w.XT = XT; w.ldxt = p.Bpad; w.dZ = dZ; w.ldz = p.Cpad;
+    w.D = D; w.C = C_shard; w.Bpad = (int)p.Bpad;
     w.nDT = p.nDT; w.nCT = p.nCT; w.k_steps = (B + TILE_K - 1) / TILE_K;
     w.dW = static_cast<uint16_t*>(dW_shard); w.lddw = lddw;
-    WS_LAUNCH(KID_DW, bwd_dw, dim3(xcd_grid(p.nDT * p.nCT)), dim3(NTHREADS), s, w);
+    FinishArgs f;
+    f.parts = direct ? nullptr : parts; f.splits = p.splits; f.split_stride = (int64_t)B * D;
+    f.B = B; f.D = D; f.dX = dX_partial; f.lddx = lddx; f.accumulate = accumulate_dx;
+    f.db_part = db_shard ? db_part : nullptr; f.n_db_parts = 4 * p.nBT; f.db_stride = p.Cpad;
+    f.C = C_shard; f.db = db_shard;
+    f.first_block = xcd_grid(p.nDT * p.nCT);
+    f.n_blocks = (f.parts || f.db_part) ? SIDE_BLOCKS : 0;
+    WS_LAUNCH(KID_DW, bwd_dw, dim3(f.first_block + f.n_blocks), dim3(NTHREADS), s, w, f);
     return launch_status();
 }
 
