@@ -76,9 +76,15 @@ __device__ __forceinline__ Operand make_operand(const uint16_t* base, int64_t ld
 // t + 1536.  Chunk set j (one chunk per thread) is "quarter j" of the tile: rows 64 j .. 64 j + 63 of
 // a KC tile, k-rows 16 j .. 16 j + 15 of a KS tile.
 
-// Chunk swizzle of a KS tile: the transposing reads of one wave touch 4 k-rows (k & 3) in each of 4
-// lane blocks 8 k-rows apart ((k >> 3) & 3), two adjacent chunks each: 32 different chunks.
-__device__ __forceinline__ int ks_swizzle(int k) { return (((k >> 3) & 3) << 1) | ((k & 3) << 3); }
+// Chunk swizzle of a KS tile.  A transposing read is served half a wave at a time; the 32 lanes of a
+// half cover 4 k-rows (k & 3) in each of 2 lane blocks 8 k-rows apart ((k >> 3) & 1), two adjacent
+// chunks and both 8-byte halves of a chunk each.  Those 16 (k-row, chunk) pairs must fall into 16
+// different chunks modulo 16 (256 bytes span all banks): k & 3 goes to chunk bits 2-3, (k >> 3) & 1 to
+// bit 1, the two adjacent chunks differ in bit 0.  Bit 4 of k only separates the two halves of the wave.
+// Bits 2 and 5 of k are left out so that the reads 4 and 32 k-rows further on keep the same pattern.
+__device__ __forceinline__ int ks_swizzle(int k) {
+    return (((k >> 3) & 1) << 1) | ((k & 3) << 2) | (((k >> 4) & 1) << 4);
+}
 
 // Per-lane byte offset of a thread's chunk in quarter 0 of the tile whose first row (KC) or first
 // column (KS) is o0, at k = 0.
@@ -126,7 +132,7 @@ struct FragAddr {
             for (int s = 0; s < 2; ++s) off[s] = (w0 + i) * 128 + (((4 * s + g) ^ sw) << 4);
         } else {
             const int x = i >> 2;                    // k-row within the group of four == (k & 3)
-            const int krow = 8 * g + x;              // (krow >> 3) & 3 == g; substeps add multiples of 32
+            const int krow = 8 * g + x;              // substeps add multiples of 32, the second read 4
 #pragma unroll
             for (int t = 0; t < NTILES; ++t) {
                 const int col = w0 + 16 * t + 4 * (i & 3);
