@@ -166,6 +166,36 @@ def main():
         "kernels": kernels,
     }
 
+    # The bridge-layer ends at this workload's shape (8 replicas feed X; 8 shards' dX_partial go back):
+    # HBM-bound copy / add kernels, timed with events on the launch stream, outside the step above.
+    R = 8 if B % 8 == 0 else 1
+    blocks = [X[i * (B // R):(i + 1) * (B // R)].clone() for i in range(R)]
+    Xg = torch.empty_like(X)
+    partials = [torch.randn((B, D), device=dev) for _ in range(8)]
+    outs = [torch.empty((B // R, D), device=dev) for _ in range(R)]
+
+    def timed(fn, iters=50):
+        for _ in range(5):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / iters
+
+    g_us = timed(lambda: ws.bridge_gather(0, blocks, Xg))
+    r_us = timed(lambda: ws.bridge_reduce_partition(partials, outs))
+    g_bytes, r_bytes = 2.0 * B * D * 2, (len(partials) + 1.0) * B * D * 4
+    result["bridge"] = {
+        "gather": {"us": round(g_us, 2), "bytes": g_bytes, "GB/s": round(g_bytes / g_us / 1e3, 1)},
+        "reduce_partition": {"us": round(r_us, 2), "bytes": r_bytes, "GB/s": round(r_bytes / r_us / 1e3, 1)},
+        "bound": "hbm", "peak_GB/s": HBM_PEAK_GBS,
+        "shape": f"{R} replica blocks of [{B // R}, {D}] bf16 -> X; {len(partials)} fp32 [B, D] partials -> {R} blocks",
+    }
+    del blocks, Xg, partials, outs
+
     if not args.no_cpu_baseline and args.workload != "cfg5":   # cfg5 keeps one shard of W only: no unsharded oracle
         # The oracle as it stands, on the host cores, on one full step of the same workload
         # (or a row sample of it when the step would take minutes).

@@ -148,6 +148,47 @@ int ws_split_fc_bwd(const void* X, int64_t ldx,
 int ws_balance_widths(int32_t N, const double* DF, const double* DM, double TG_flop, double TG_mem,
                       int32_t C, int32_t* widths, int32_t* feasible);
 
+/* ---- The ends of the bridge layer on one device (Section 3.2.3) ------------------------------
+ * Between two TaskGraphs with different strategies the paper inserts a bridge layer that gathers the
+ * distributed outputs of the first so that the second reads a complete tensor: for `replicate` the
+ * parts are different batches and are concatenated along the batch dimension, for `split` they are
+ * slices along the split dimension and are concatenated there.  In the workload of this library the
+ * replicated feature extractor hands its per-replica feature blocks to the split classifier
+ * (gather along the batch: this builds X), and on the way back the shards' dX_partial are summed
+ * and cut along the batch again.  These entry points are what ONE device runs once the parts are
+ * in its memory; moving them between devices is not part of this library.
+ * The part tables (arrays of pointers, pitches, extents) are HOST arrays; the pointers in them
+ * are DEVICE pointers.  At most WS_BRIDGE_MAX_PARTS parts per call (else WS_ERR_RANGE). */
+#define WS_BRIDGE_MAX_PARTS 64
+
+/* Forward end: out = concatenation of n parts.
+ *   dim = 0  replicate pattern: part p is [extents[p]][other], parts stack along the rows (batch)
+ *   dim = 1  split pattern:     part p is [other][extents[p]], parts stack along the columns
+ *   ld_parts[p], ld_out  row pitches in elements; elem_bytes 2 or 4; extents may be uneven or 0
+ * Bytes are copied unchanged.  Every pointer and pitch must be a multiple of elem_bytes
+ * (WS_ERR_ALIGN); wider alignment is detected and used.  out must not overlap any part. */
+int ws_bridge_gather(int32_t dim, const void* const* parts, const int64_t* ld_parts,
+                     const int32_t* extents, int32_t n, int32_t other, int32_t elem_bytes,
+                     void* out, int64_t ld_out, void* stream);
+
+/* Backward end in front of a split TaskGraph: the S shards each hold a partial gradient of the
+ * gathered tensor (fp32 [B][ld_partials[s]], B = sum of rows[]; ws_split_fc_bwd's dX_partial);
+ * replica r receives rows [rows[0] + .. + rows[r-1], +rows[r]) of their sum:
+ *   out_parts[r][i][d] = sum_{s = 0 .. S-1, in this order} partials[s][row0_r + i][d]   fp32
+ * D a multiple of 4; all pointers 16-byte aligned, pitches multiples of 4 and >= D. */
+int ws_bridge_reduce_partition(const float* const* partials, const int64_t* ld_partials, int32_t S,
+                               int32_t D, float* const* out_parts, const int64_t* ld_out,
+                               const int32_t* rows, int32_t R, void* stream);
+
+/* The fusion rule of Section 3.2.3 (HOST pointers only; no GPU work): when the bridge gathers
+ * along the dimension along which the successor TaskGraph partitions its input, the gather and
+ * the partition are both removed.  Reading taken here: they cancel only if the cuts coincide as
+ * well (same number of parts, same extents), because otherwise data still has to change devices.
+ * *fusable = 1 if both operations can be dropped, else 0. */
+int ws_bridge_fusable(int32_t gather_dim, int32_t n_src, const int64_t* src_extents,
+                      int32_t partition_dim, int32_t n_dst, const int64_t* dst_extents,
+                      int32_t* fusable);
+
 /* Optional per-kernel timing, for benchmarks (not part of the paper's method; host-side state,
  * not thread safe).  ws_profile_enable(n) creates a pool of n event pairs (n <= 0 switches
  * timing off and frees the pool); while the pool lasts, every kernel the library launches is

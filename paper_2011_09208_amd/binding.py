@@ -53,10 +53,20 @@ lib.ws_balance_widths.restype = ctypes.c_int
 lib.ws_balance_widths.argtypes = [_i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
                                   ctypes.c_double, ctypes.c_double, _i32, ctypes.POINTER(_i32), ctypes.POINTER(_i32)]
 
+lib.ws_bridge_gather.restype = ctypes.c_int
+lib.ws_bridge_gather.argtypes = [_i32, ctypes.POINTER(_p), ctypes.POINTER(_i64), ctypes.POINTER(_i32), _i32, _i32, _i32,
+                                 _p, _i64, _p]
+lib.ws_bridge_reduce_partition.restype = ctypes.c_int
+lib.ws_bridge_reduce_partition.argtypes = [ctypes.POINTER(_p), ctypes.POINTER(_i64), _i32, _i32, ctypes.POINTER(_p),
+                                           ctypes.POINTER(_i64), ctypes.POINTER(_i32), _i32, _p]
+lib.ws_bridge_fusable.restype = ctypes.c_int
+lib.ws_bridge_fusable.argtypes = [_i32, _i32, ctypes.POINTER(_i64), _i32, _i32, ctypes.POINTER(_i64), ctypes.POINTER(_i32)]
+
 EXPORTS = ["ws_status_string", "ws_version", "ws_fwd_workspace_bytes", "ws_split_fc_fwd",
            "ws_combine_partials", "ws_bwd_workspace_bytes", "ws_split_fc_bwd",
            "ws_profile_enable", "ws_profile_reset", "ws_profile_kernel_count", "ws_profile_kernel_name",
-           "ws_profile_read", "ws_balance_widths"]
+           "ws_profile_read", "ws_balance_widths",
+           "ws_bridge_gather", "ws_bridge_reduce_partition", "ws_bridge_fusable"]
 
 
 class WhaleSplitError(RuntimeError):
@@ -156,3 +166,40 @@ def balance_widths(C, DF, DM, TG_flop, TG_mem):
     ok = _i32(0)
     _check(lib.ws_balance_widths(n, df, dm, float(TG_flop), float(TG_mem), int(C), w, ctypes.byref(ok)))
     return list(w), bool(ok.value)
+
+
+def bridge_gather(dim, parts, out):
+    """Concatenates 2-D device tensors `parts` (same dtype, 2 or 4 bytes per element) into `out` along
+    dim 0 (rows: the replicate pattern) or dim 1 (columns: the split pattern)."""
+    n = len(parts)
+    other = out.shape[1 - dim]
+    ptrs = (_p * n)(*[p.data_ptr() for p in parts])
+    lds = (_i64 * n)(*[p.stride(0) if p.shape[0] > 1 else max(p.shape[1], p.stride(0)) for p in parts])
+    ext = (_i32 * n)(*[p.shape[dim] for p in parts])
+    for p in parts:
+        assert p.dtype == out.dtype and p.dim() == 2 and p.shape[1 - dim] == other
+        assert p.shape[1] <= 1 or p.stride(1) == 1
+    _check(lib.ws_bridge_gather(int(dim), ptrs, lds, ext, n, int(other), out.element_size(), _ptr(out),
+                                out.stride(0), _stream()))
+
+
+def bridge_reduce_partition(partials, out_parts):
+    """out_parts[r] (fp32 [rows_r, D]) = rows of sum(partials) (fp32 [B, D] each), B = sum of rows_r."""
+    S, R = len(partials), len(out_parts)
+    D = partials[0].shape[1]
+    pp = (_p * S)(*[p.data_ptr() for p in partials])
+    pl = (_i64 * S)(*[p.stride(0) for p in partials])
+    op = (_p * R)(*[o.data_ptr() for o in out_parts])
+    ol = (_i64 * R)(*[o.stride(0) if o.shape[0] > 1 else max(D, o.stride(0)) for o in out_parts])
+    rows = (_i32 * R)(*[o.shape[0] for o in out_parts])
+    assert sum(o.shape[0] for o in out_parts) <= min(p.shape[0] for p in partials)
+    _check(lib.ws_bridge_reduce_partition(pp, pl, S, int(D), op, ol, rows, R, _stream()))
+
+
+def bridge_fusable(gather_dim, src_extents, partition_dim, dst_extents):
+    a = (_i64 * len(src_extents))(*[int(v) for v in src_extents])
+    b = (_i64 * len(dst_extents))(*[int(v) for v in dst_extents])
+    ok = _i32(0)
+    _check(lib.ws_bridge_fusable(int(gather_dim), len(src_extents), a, int(partition_dim), len(dst_extents), b,
+                                 ctypes.byref(ok)))
+    return bool(ok.value)
