@@ -12,6 +12,7 @@ stream inside the timed region), the per-kernel breakdown, and the fp64 oracle t
 host cores as a CPU baseline.
 """
 import argparse
+import ctypes
 import json
 import os
 import sys
@@ -63,10 +64,12 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; there is no CPU fallback")
 
-    # cfg5 times its first shard only (50 000 of 400 000 classes); the other rows of W are not kept
-    p = inputs.make_config(args.workload, w_rows=50_000 if args.workload == "cfg5" else None)
+    # cfg5 and million time their first shard only (50 000 of 400 000, 125 000 of 1 000 000 classes);
+    # the other rows of W are not kept
+    first_shard_only = {"cfg5": 50_000, "million": 125_000}
+    p = inputs.make_config(args.workload, w_rows=first_shard_only.get(args.workload))
     B, D = p.B, p.D
-    shards = p.shards if args.workload != "cfg5" else p.shards[:1]
+    shards = p.shards if args.workload not in first_shard_only else p.shards[:1]
     C = p.W_bits.shape[0]
     dev = torch.device("cuda:0")
     X = torch.from_numpy(p.X_bits.view(np.int16)).to(dev).view(torch.bfloat16)
@@ -185,8 +188,12 @@ def main():
         e1.synchronize()
         return e0.elapsed_time(e1) * 1e3 / iters
 
-    g_us = timed(lambda: ws.bridge_gather(0, blocks, Xg))
-    r_us = timed(lambda: ws.bridge_reduce_partition(partials, outs))
+    # arguments marshalled once: at these sizes a call is a few microseconds of GPU time
+    g_args = ws.bridge_gather_args(0, blocks, Xg)
+    r_args = ws.bridge_reduce_partition_args(partials, outs)
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    g_us = timed(lambda: ws.lib.ws_bridge_gather(*g_args, stream))
+    r_us = timed(lambda: ws.lib.ws_bridge_reduce_partition(*r_args, stream))
     g_bytes, r_bytes = 2.0 * B * D * 2, (len(partials) + 1.0) * B * D * 4
     result["bridge"] = {
         "gather": {"us": round(g_us, 2), "bytes": g_bytes, "GB/s": round(g_bytes / g_us / 1e3, 1)},
@@ -196,7 +203,7 @@ def main():
     }
     del blocks, Xg, partials, outs
 
-    if not args.no_cpu_baseline and args.workload != "cfg5":   # cfg5 keeps one shard of W only: no unsharded oracle
+    if not args.no_cpu_baseline and args.workload not in first_shard_only:   # one shard of W only: no unsharded oracle
         # The oracle as it stands, on the host cores, on one full step of the same workload
         # (or a row sample of it when the step would take minutes).
         from oracle import oracle

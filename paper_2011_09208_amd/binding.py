@@ -168,32 +168,41 @@ def balance_widths(C, DF, DM, TG_flop, TG_mem):
     return list(w), bool(ok.value)
 
 
-def bridge_gather(dim, parts, out):
-    """Concatenates 2-D device tensors `parts` (same dtype, 2 or 4 bytes per element) into `out` along
-    dim 0 (rows: the replicate pattern) or dim 1 (columns: the split pattern)."""
+def bridge_gather_args(dim, parts, out):
+    """The argument tuple of ws_bridge_gather (without the stream) for 2-D device tensors."""
     n = len(parts)
     other = out.shape[1 - dim]
-    ptrs = (_p * n)(*[p.data_ptr() for p in parts])
-    lds = (_i64 * n)(*[p.stride(0) if p.shape[0] > 1 else max(p.shape[1], p.stride(0)) for p in parts])
-    ext = (_i32 * n)(*[p.shape[dim] for p in parts])
     for p in parts:
         assert p.dtype == out.dtype and p.dim() == 2 and p.shape[1 - dim] == other
         assert p.shape[1] <= 1 or p.stride(1) == 1
-    _check(lib.ws_bridge_gather(int(dim), ptrs, lds, ext, n, int(other), out.element_size(), _ptr(out),
-                                out.stride(0), _stream()))
+    ptrs = (_p * n)(*[p.data_ptr() for p in parts])
+    lds = (_i64 * n)(*[p.stride(0) if p.shape[0] > 1 else max(p.shape[1], p.stride(0)) for p in parts])
+    ext = (_i32 * n)(*[p.shape[dim] for p in parts])
+    return (int(dim), ptrs, lds, ext, n, int(other), out.element_size(), _ptr(out), out.stride(0))
 
 
-def bridge_reduce_partition(partials, out_parts):
-    """out_parts[r] (fp32 [rows_r, D]) = rows of sum(partials) (fp32 [B, D] each), B = sum of rows_r."""
+def bridge_gather(dim, parts, out):
+    """Concatenates 2-D device tensors `parts` (same dtype, 2 or 4 bytes per element) into `out` along
+    dim 0 (rows: the replicate pattern) or dim 1 (columns: the split pattern)."""
+    _check(lib.ws_bridge_gather(*bridge_gather_args(dim, parts, out), _stream()))
+
+
+def bridge_reduce_partition_args(partials, out_parts):
+    """The argument tuple of ws_bridge_reduce_partition (without the stream)."""
     S, R = len(partials), len(out_parts)
     D = partials[0].shape[1]
+    assert sum(o.shape[0] for o in out_parts) <= min(p.shape[0] for p in partials)
     pp = (_p * S)(*[p.data_ptr() for p in partials])
     pl = (_i64 * S)(*[p.stride(0) for p in partials])
     op = (_p * R)(*[o.data_ptr() for o in out_parts])
     ol = (_i64 * R)(*[o.stride(0) if o.shape[0] > 1 else max(D, o.stride(0)) for o in out_parts])
     rows = (_i32 * R)(*[o.shape[0] for o in out_parts])
-    assert sum(o.shape[0] for o in out_parts) <= min(p.shape[0] for p in partials)
-    _check(lib.ws_bridge_reduce_partition(pp, pl, S, int(D), op, ol, rows, R, _stream()))
+    return (pp, pl, S, int(D), op, ol, rows, R)
+
+
+def bridge_reduce_partition(partials, out_parts):
+    """out_parts[r] (fp32 [rows_r, D]) = rows of sum(partials) (fp32 [B, D] each), B = sum of rows_r."""
+    _check(lib.ws_bridge_reduce_partition(*bridge_reduce_partition_args(partials, out_parts), _stream()))
 
 
 def bridge_fusable(gather_dim, src_extents, partition_dim, dst_extents):

@@ -87,19 +87,20 @@ class SplitFcInputs:
 
 
 def make_inputs(name, B, D, C, *, x_sigma=1.0, x_relu=False, w_sigma=0.02, labels="uniform",
-                shards=None, seed=0, bias_sigma=None, w_rows=None) -> SplitFcInputs:
+                shards=None, seed=0, bias_sigma=None, w_rows=None, draw_discarded=True) -> SplitFcInputs:
     """Draw X [B, D], W [C, D] (or only its first `w_rows` classes), labels [B].
 
     `w_rows` lets a test keep only the leading classes of a very wide layer (the
     remaining rows are still drawn and discarded so the stream position of the
-    labels does not depend on it).
+    labels does not depend on it; with `draw_discarded=False` they are skipped,
+    which saves a minute for a 1M-class layer and makes the labels depend on `w_rows`).
     """
     rng = np.random.Generator(np.random.PCG64(seed))
     X_bits = _draw_normal_bf16(rng, B, D, x_sigma, x_relu)
     keep = C if w_rows is None else int(w_rows)
     W_bits = np.empty((keep, D), dtype=np.uint16)
     chunk = 8192
-    for r0 in range(0, C, chunk):
+    for r0 in range(0, C if draw_discarded else keep, chunk):
         r1 = min(C, r0 + chunk)
         blk = _draw_normal_bf16(rng, r1 - r0, D, w_sigma, False)
         if r0 < keep:
@@ -138,6 +139,9 @@ CONFIGS = {
     # large-vocabulary head: first 50 000 of 400 000 classes
     "cfg5": dict(B=8192, D=1024, C=400_000, x_sigma=1.0, w_sigma=0.02, labels=("zipf", 1.0),
                  shards=equal_shards(400_000, 8)),
+    # the paper's second workload: a 1M-class layer cut 8 ways (Section 5.1.2, the 1M-class hybrid run)
+    "million": dict(B=1024, D=2048, C=1_000_000, x_relu=True, w_sigma=0.01, labels="uniform",
+                    shards=equal_shards(1_000_000, 8), draw_discarded=False),
     # headline shape: the whole 100K-class layer as one shard at B = 1024
     "headline": dict(B=1024, D=2048, C=100_000, x_relu=True, w_sigma=0.01, labels="uniform",
                      shards=[(0, 100_000)]),

@@ -189,6 +189,38 @@ def test_large_vocab_head_shard(H):
         assert v <= H.GRAD_REL_TO_MAX, (k, v)
 
 
+def test_million_class_shard_full_size(H):
+    """The paper's second workload: a 1M-class layer cut 8 ways (Section 5.1.2), one GPU's share at its
+    real shape: B = 1024, D = 2048, classes [0, 125 000) of 1 000 000, uniform labels (about one row in
+    eight has its label here).  Evaluated like the large-vocabulary shard above: forward statistics
+    against the oracle's for every row; the backward call gets a log-sum-exp the oracle makes up for the
+    seven missing shards (equal mass in each) and is compared element by element."""
+    from oracle import oracle
+    off, c = 0, 125_000
+    p = inputs.make_config("million", w_rows=c)
+    H.say(f"[parity] 1M-class shard: B={p.B} D={p.D} C_shard={c} of {p.C}")
+    X = inputs.bf16_bits_to_f64(p.X_bits)
+    W = inputs.bf16_bits_to_f64(p.W_bits)
+    y = p.labels.astype(np.int64)
+    m, s, t = oracle.partials(X, W, None, y, off)
+    lse_in = (m + np.log(s) + math.log(8.0)).astype(np.float32)
+    got = H.run_step(p.X_bits, p.W_bits, None, p.labels, [(off, c)], g=1.0, lse_override=lse_in)
+    inside = (y >= off) & (y < off + c)
+    assert 0.08 < inside.mean() < 0.18
+    assert np.all(got["t"][0][~inside] == 0.0)
+    zscale = max(1.0, float(np.max(np.abs(m))))
+    assert np.max(np.abs(got["m"][0] - m)) <= H.LSE_ABS * zscale
+    assert np.max(np.abs(got["s"][0] - s) / s) <= 1e-3 + H.LSE_ABS * zscale
+    assert np.max(np.abs(got["t"][0] - t)) <= H.LSE_ABS * zscale
+    ref = oracle.shard_grads(X, W, None, lse_in.astype(np.float64), y, off, 1.0)
+    rep = {k: H.max_rel_to_max(a, b) for k, a, b in (("dX", got["dX"], ref["dX_partial"]),
+                                                      ("dW", got["dW"][0], ref["dW"]),
+                                                      ("db", got["db"][0], ref["db"]))}
+    H.say("[parity] 1M-class shard: " + " ".join(f"{k}={v:.2e}" for k, v in rep.items()))
+    for k, v in rep.items():
+        assert v <= H.GRAD_REL_TO_MAX, (k, v)
+
+
 def test_padded_pitches_stream_and_accumulate(H):
     """Row pitches larger than the row length for every matrix argument, a side stream, loss_mean, and
     accumulate_dx on top of a pre-filled dX: the library must honour pitches, touch nothing in the padding,
@@ -234,3 +266,62 @@ def test_padded_pitches_stream_and_accumulate(H):
     assert H.max_rel_to_max(dW[:, :D].astype(np.float64), ref["dW"]) <= H.GRAD_REL_TO_MAX
     assert H.max_rel_to_max(db.cpu().numpy(), ref["db"]) <= H.GRAD_REL_TO_MAX
     assert torch.isnan(Xp[:, D:]).all() and torch.isnan(Wp[:, D:]).all()      # inputs never modified
+
+
+def test_graph_capture_replays_match_eager(H):
+    """The three calls allocate nothing, never synchronise and clear no memory with memset nodes, so a
+    whole step can be captured into a HIP graph.  Every replay (with the program's own eager work and
+    synchronisations between the replays) must reproduce the eager results bit for bit."""
+    import torch
+    from paper_2011_09208_amd import binding as ws
+    p = inputs.make_inputs("graph", 300, 256, 3000, w_sigma=0.2, bias_sigma=0.5, seed=33)
+    H.say(f"[parity] graph capture: B={p.B} D={p.D} C={p.C}, two shards")
+    dev = torch.device("cuda")
+    shards = [(0, 1100), (1100, 1900)]
+    X, W = H.dev_bf16(p.X_bits), H.dev_bf16(p.W_bits)
+    bias = torch.from_numpy(p.bias).to(dev)
+    y = torch.from_numpy(p.labels).to(dev)
+    B, D = p.B, p.D
+    m, s, t = (torch.empty((2, B), device=dev) for _ in range(3))
+    lse, loss, mean = torch.empty(B, device=dev), torch.empty(B, device=dev), torch.empty(1, device=dev)
+    dX = torch.empty((B, D), device=dev)
+    dW = torch.empty((p.C, D), device=dev, dtype=torch.bfloat16)
+    db = torch.empty(p.C, device=dev)
+    work = torch.empty(max(max(ws.fwd_workspace_bytes(B, D, c), ws.bwd_workspace_bytes(B, D, c)) for _, c in shards),
+                       dtype=torch.uint8, device=dev)
+    outs = (m, s, t, lse, loss, mean, dX, dW, db)
+
+    def step():
+        for i, (off, c) in enumerate(shards):
+            ws.split_fc_fwd(X, W[off:off + c], bias[off:off + c], y, off, m[i], s[i], t[i], work)
+        ws.combine_partials(m, s, t, lse, loss, mean)
+        for i, (off, c) in enumerate(shards):
+            ws.split_fc_bwd(X, W[off:off + c], bias[off:off + c], lse, y, off, 0.25, dX, i > 0, dW[off:off + c],
+                            db[off:off + c], work)
+
+    step()
+    torch.cuda.synchronize()
+    eager = [o.clone() for o in outs]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                   # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for o in outs:
+            o.fill_(float("nan")) if o.dtype != torch.bfloat16 else o.fill_(1.0)
+        work.fill_(0xFF)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for o, e in zip(outs, eager):
+            assert torch.equal(o.view(torch.int16) if o.dtype == torch.bfloat16 else o.view(torch.int32),
+                               e.view(torch.int16) if e.dtype == torch.bfloat16 else e.view(torch.int32)), rep
+    ref = H.oracle_step(p.X_bits, p.W_bits, p.bias, p.labels, shards, g=0.25)
+    assert np.max(np.abs(lse.cpu().numpy() - ref["lse"])) <= H.LSE_ABS * max(1.0, np.abs(ref["lse"]).max())
+    assert H.max_rel_to_max(dX.cpu().numpy(), ref["dX"]) <= H.GRAD_REL_TO_MAX
