@@ -130,6 +130,19 @@ int ws_split_fc_bwd(const void* X, int64_t ldx,
                     float* db_shard,
                     void* workspace, size_t workspace_bytes, void* stream);
 
+/* Predictions of one shard.  The paper's split listing (Section 3.1.2) ends the split scope with
+ * predictions = Softmax(logits); with the combined log-sum-exp of all shards every shard can write
+ * its own columns of that matrix without seeing another shard's logits:
+ *   P[i][c] = exp(z[i][c] - logsumexp[i])      bf16 [B][ldp], c in [0, C_shard)
+ * The shards' P concatenate along the split dimension (ws_bridge_gather, dim = 1) to the full
+ * softmax; each row of it sums to 1.  The logits are recomputed exactly as in the forward call
+ * and are not stored.  P 16-byte aligned, ldp >= C_shard and a multiple of 8; columns beyond
+ * C_shard are not touched.  No workspace. */
+int ws_split_fc_predict(const void* X, int64_t ldx, const void* W_shard, int64_t ldw,
+                        const float* b_shard, const float* logsumexp,
+                        int32_t B, int32_t D, int32_t C_shard,
+                        void* P, int64_t ldp, void* stream);
+
 /* Hardware-aware shard widths (HOST pointers only; no GPU work).  Section 3.3.1: a `split`
  * TaskGraph is balanced over devices of unequal capacity by uneven sharding in the splitting
  * dimension; load ratios proportional to the devices' FLOP/s minimise the formula given there,

@@ -171,3 +171,9 @@ def unsharded_chunked(X, W, b, y, g=1.0, rows_per_chunk=512, want_dW=True):
         db += part["db"]
     return {"lse": lse, "loss": loss, "loss_mean": loss.mean() if B else _F(0.0),
             "dX": dX, "dW": dW, "db": db}
+
+
+def predictions(X, W_s, b_s, lse):
+    """The shard's columns of Softmax(logits) (the last line of the paper's split listing,
+    Section 3.1.2), given the log-sum-exp over ALL classes: P[i, c] = exp(Z_ic - lse_i)."""
+    return np.exp(logits(X, W_s, b_s) - _as64(lse)[:, None])

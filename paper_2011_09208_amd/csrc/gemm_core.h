@@ -373,8 +373,8 @@ __device__ __forceinline__ void acc_to_lds_bf16(const acc_t& acc, char* lds) {
 }
 
 // Writes the LDS tile to out[n][m] (row pitch ld elements, `out` = address of element (0, 0) of the
-// tile), rows n < n_valid and columns m < m_valid only (m_valid a multiple of 8).  A wave stores two
-// whole 512-byte rows per instruction.
+// tile), rows n < n_valid and columns m < m_valid only.  A wave stores two whole 512-byte rows per
+// instruction; a chunk that m_valid cuts (m_valid not a multiple of 8) goes out element by element.
 __device__ __forceinline__ void lds_tile_store_rows(const char* lds, uint16_t* out, int64_t ld, int n_valid,
                                                     int m_valid) {
     const int tid = threadIdx.x;
@@ -387,7 +387,15 @@ __device__ __forceinline__ void lds_tile_store_rows(const char* lds, uint16_t* o
             const int g = out_tile_swizzle(n);
             u32x4 v = *reinterpret_cast<const u32x4*>(lds + n * 512 + ((cq ^ (g >> 1)) << 4));
             if (g & 1) v = __builtin_shufflevector(v, v, 2, 3, 0, 1);
-            __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(out + (int64_t)n * ld + cq * 8));
+            uint16_t* o = out + (int64_t)n * ld + cq * 8;
+            if (cq * 8 + 8 <= m_valid) {
+                __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(o));
+            } else {
+                const int left = m_valid - cq * 8;
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (e < left) o[e] = (uint16_t)(v[e >> 1] >> (16 * (e & 1)));
+            }
         }
     }
 }

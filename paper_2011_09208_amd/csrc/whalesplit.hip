@@ -8,6 +8,7 @@
 //   bwd_recompute_dz   same GEMM again, epilogue dz = g (exp(z - lse) - onehot) stored as bf16
 //                      [row][class]; column sums of the tile (db partials); its surplus workgroups
 //                      write X^T for the dW contraction
+//   predict_probs      softmax probabilities of the shard's classes, exp(z - lse), bf16
 //   bwd_dx             dX_partial = dz . W_s, split along the class contraction; partial sums
 //   bwd_dw             dW_s = dz^T . X; its surplus workgroups sum the split-K partials of dX
 //                      (optionally accumulating into the caller's dX) and the db partials
@@ -344,6 +345,39 @@ __global__ __launch_bounds__(NTHREADS) void bwd_recompute_dz(FcArgs a, const flo
     lds_tile_store_rows(lds, dZ + (int64_t)bt * TILE_N * ldz + ct * TILE_M, ldz, TILE_N, TILE_M);
 }
 
+// Predictions of the shard: P[i][c] = exp(z[i][c] - lse[i]) as bf16, the same GEMM and staging as
+// bwd_recompute_dz without the one-hot term, written straight into the caller's [B][ldp] matrix
+// (ragged edges cut at B and C).
+__global__ __launch_bounds__(NTHREADS) void predict_probs(FcArgs a, const float* __restrict__ logsumexp,
+                                                           uint16_t* __restrict__ P, int64_t ldp) {
+    __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
+    float* sbias = reinterpret_cast<float*>(lds);
+    const int tile = xcd_logical_tile(a.nBT * a.nCT);
+    if (tile < 0) return;
+    const int ct = tile / a.nBT, bt = tile % a.nBT;
+
+    acc_t acc;
+    logits_tile(acc, a, ct, bt, lds, sbias);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wn = wave & 3, jl = lane & 15;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int row = bt * TILE_N + wn * WAVE_N + 16 * nt + jl;
+        const float shift = row < a.B ? -logsumexp[row] * LOG2E : 0.0f;      // rows beyond B are not stored
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[mt][nt][v] = __builtin_amdgcn_exp2f(fmaf(acc[mt][nt][v], LOG2E, shift));
+    }
+    __syncthreads();                       // the bias staging area is about to be overwritten
+    acc_to_lds_bf16(acc, lds);
+    __syncthreads();
+    const int b_left = a.B - bt * TILE_N, c_left = a.C - ct * TILE_M;
+    lds_tile_store_rows(lds, P + (int64_t)bt * TILE_N * ldp + ct * TILE_M, ldp, b_left < TILE_N ? b_left : TILE_N,
+                        c_left < TILE_M ? c_left : TILE_M);
+}
+
 struct DxArgs {
     const uint16_t* dZ; int64_t ldz;     // [Bpad][Cpad]
     const uint16_t* W; int64_t ldw;      // [C][D]
@@ -528,9 +562,10 @@ static int check_fc_common(const void* X, int64_t ldx, const void* W, int64_t ld
 // When enabled, every kernel launch is bracketed by a pair of events recorded on the launch stream.
 // The pairs come from a pool created by ws_profile_enable; when the pool is used up, launches go
 // untimed.  Not thread safe; meant for benchmarks.
-enum KernelId { KID_FWD = 0, KID_MERGE, KID_COMBINE, KID_MEAN, KID_DZ, KID_DX, KID_DW, KID_COUNT };
+enum KernelId { KID_FWD = 0, KID_MERGE, KID_COMBINE, KID_MEAN, KID_DZ, KID_DX, KID_DW, KID_PREDICT, KID_COUNT };
 static const char* const kKernelNames[KID_COUNT] = {"fwd_logits_stats", "merge_class_tiles", "combine_partials",
-                                                    "mean_loss", "bwd_recompute_dz", "bwd_dx", "bwd_dw"};
+                                                    "mean_loss", "bwd_recompute_dz", "bwd_dx", "bwd_dw",
+                                                    "predict_probs"};
 struct ProfState {
     bool on = false;
     int capacity = 0, used = 0;
@@ -697,6 +732,29 @@ int ws_split_fc_bwd(const void* X, int64_t ldx, const void* W_shard, int64_t ldw
     f.first_block = xcd_grid(p.nDT * p.nCT);
     f.n_blocks = (f.parts || f.db_part) ? SIDE_BLOCKS : 0;
     WS_LAUNCH(KID_DW, bwd_dw, dim3(f.first_block + f.n_blocks), dim3(NTHREADS), s, w, f);
+    return launch_status();
+}
+
+int ws_split_fc_predict(const void* X, int64_t ldx, const void* W_shard, int64_t ldw, const float* b_shard,
+                        const float* logsumexp, int32_t B, int32_t D, int32_t C_shard, void* P, int64_t ldp,
+                        void* stream) {
+    if (!X || !W_shard || !logsumexp || !P) return WS_ERR_NULL;
+    if (!shape_ok(B, D, C_shard)) return WS_ERR_SHAPE;
+    if (ldx < D || ldw < D || ldp < C_shard) return WS_ERR_SHAPE;
+    if (!fits_32bit_offsets(B, ldx) || !fits_32bit_offsets(C_shard, ldw)) return WS_ERR_SHAPE;
+    if (!aligned(X, 16) || !aligned(W_shard, 16) || !aligned(P, 16) || ldx % 8 || ldw % 8 || ldp % 8) return WS_ERR_ALIGN;
+    if (!aligned(logsumexp, 4) || (b_shard && !aligned(b_shard, 4))) return WS_ERR_ALIGN;
+    FcArgs a;
+    a.X = static_cast<const uint16_t*>(X); a.ldx = ldx;
+    a.W = static_cast<const uint16_t*>(W_shard); a.ldw = ldw;
+    a.bias = b_shard; a.labels = nullptr;
+    a.B = B; a.D = D; a.C = C_shard; a.class_offset = 0;
+    a.Bpad = (int)round_up(B, 256);
+    a.nBT = a.Bpad / 256;
+    a.nCT = (int)(round_up(C_shard, 256) / 256);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    WS_LAUNCH(KID_PREDICT, predict_probs, dim3(xcd_grid(a.nBT * a.nCT)), dim3(NTHREADS), s, a, logsumexp,
+              static_cast<uint16_t*>(P), ldp);
     return launch_status();
 }
 

@@ -95,3 +95,17 @@ def test_combine_validation(ws):
     assert f(A, A, A, 70000, 4, 4, A, A, None, None) == 4
     assert f(A + 1, A, A, 1, 4, 4, A, A, None, None) == 3
     assert f(A, A, A, 1, 4, 4, A, A, A + 2, None) == 3
+
+
+def test_predict_argument_validation(ws):
+    E = {ws.status_string(i): i for i in range(7)}
+
+    def pred(X=A, ldx=64, W=A, ldw=64, b=None, lse=A, B=4, D=64, C=8, P=A, ldp=8):
+        return ws.lib.ws_split_fc_predict(X, ldx, W, ldw, b, lse, B, D, C, P, ldp, None)
+
+    assert pred(P=None) == E["WS_ERR_NULL"] and pred(lse=None) == E["WS_ERR_NULL"]
+    assert pred(D=65) == E["WS_ERR_SHAPE"] and pred(C=0) == E["WS_ERR_SHAPE"]
+    assert pred(C=9, ldp=8) == E["WS_ERR_SHAPE"]                  # pitch below the shard width
+    assert pred(C=9, ldp=12) == E["WS_ERR_ALIGN"]                 # pitch not a multiple of 8
+    assert pred(P=A + 2) == E["WS_ERR_ALIGN"] and pred(lse=A + 2) == E["WS_ERR_ALIGN"]
+    assert pred(B=1 << 20, ldx=4096) == E["WS_ERR_SHAPE"]         # X beyond 32-bit offsets

@@ -325,3 +325,60 @@ def test_graph_capture_replays_match_eager(H):
     ref = H.oracle_step(p.X_bits, p.W_bits, p.bias, p.labels, shards, g=0.25)
     assert np.max(np.abs(lse.cpu().numpy() - ref["lse"])) <= H.LSE_ABS * max(1.0, np.abs(ref["lse"]).max())
     assert H.max_rel_to_max(dX.cpu().numpy(), ref["dX"]) <= H.GRAD_REL_TO_MAX
+
+
+def _predict_parity(H, p, shards, pad=0, tag=""):
+    """Predictions of every shard against the oracle's, given the oracle's combined log-sum-exp rounded
+    to fp32 (an input).  Relative gate: bf16 rounding of P (2^-9) plus the effect of the logits' own
+    fp32 rounding on exp (the lse gate, scaled like it), plus a floor for values that underflow bf16."""
+    import torch
+    from oracle import oracle
+    from paper_2011_09208_amd import binding as ws
+    X64, W64 = inputs.bf16_bits_to_f64(p.X_bits), inputs.bf16_bits_to_f64(p.W_bits)
+    b64 = None if p.bias is None else p.bias.astype(np.float64)
+    Z = oracle.logits(X64, W64, b64)
+    lse32 = oracle.logsumexp_rows(Z).astype(np.float32)
+    zscale = max(1.0, float(np.max(np.abs(Z))))
+    del Z
+    X, W = H.dev_bf16(p.X_bits), H.dev_bf16(p.W_bits)
+    bias = None if p.bias is None else torch.from_numpy(p.bias).cuda()
+    lse = torch.from_numpy(lse32).cuda()
+    worst = 0.0
+    row_sum = np.zeros(p.B)
+    for off, c in shards:
+        ldp = (c + 7) // 8 * 8 + pad
+        Pbuf = torch.full((p.B, ldp), 3.0, dtype=torch.bfloat16, device="cuda")
+        P = Pbuf[:, :c]
+        ws.split_fc_predict(X, W[off:off + c], None if bias is None else bias[off:off + c], lse, P)
+        torch.cuda.synchronize()
+        got = H.bf16_to_f64(Pbuf)
+        assert np.all(got[:, c:] == 3.0), f"{tag}: columns beyond the shard were written"
+        ref = oracle.predictions(X64, W64[off:off + c], None if b64 is None else b64[off:off + c],
+                                 lse32.astype(np.float64))
+        err = np.abs(got[:, :c] - ref)
+        tol = (2.0 ** -8 + 2 * H.LSE_ABS * zscale) * ref + 1e-38
+        assert np.all(err <= tol), (tag, off, c, float(np.max(err / (ref + 1e-300))))
+        worst = max(worst, float(np.max(err / (ref + 1e-30))))
+        row_sum += got[:, :c].sum(axis=1)
+    assert np.max(np.abs(row_sum - 1.0)) <= 2.0 ** -8 + 2 * H.LSE_ABS * zscale, tag
+    H.say(f"[parity] {tag}: predictions max rel err {worst:.2e}, max |row sum - 1| {np.max(np.abs(row_sum - 1.0)):.2e}")
+
+
+def test_predictions_small_and_ragged(H):
+    p = inputs.make_config("cfg1")
+    H.say("[parity] predictions cfg1")
+    _predict_parity(H, p, p.shards, tag="predict cfg1")
+    for B, D, C, shards, seed in [(300, 128, 777, [(0, 5), (5, 515), (520, 257)], 41),
+                                  (257, 64, 1031, [(0, 1031)], 42),
+                                  (1, 64, 9, [(0, 1), (1, 8)], 43)]:
+        q = inputs.make_inputs("predict", B, D, C, w_sigma=0.4, bias_sigma=1.0, seed=seed)
+        H.say(f"[parity] predictions ragged: B={B} D={D} C={C} shards={shards}")
+        _predict_parity(H, q, shards, pad=8, tag=f"predict {B}x{D}x{C}")
+
+
+def test_predictions_full_size_uneven_shards(H):
+    """cfg4 at full size: B = 1024, D = 2048, C = 100 000 as the uneven shards (37 500, 12 500, 37 500, 12 500),
+    every element of every shard against the oracle."""
+    p = inputs.make_config("cfg4")
+    H.say(f"[parity] predictions cfg4: B={p.B} D={p.D} C={p.C} shards={p.shards}")
+    _predict_parity(H, p, p.shards, tag="predict cfg4")

@@ -269,3 +269,31 @@ def test_paper_sizes_fixture():
     assert round(2048 * C * 4 / 2**20) != vals["fc_param_mb"]         # without the bias it would print 781
     share = vals["fc_param_mb"] / (vals["fc_param_mb"] + vals["resnet50_param_mb"])
     assert round(100 * share, 1) == vals["sync_reduction_percent"]
+
+
+# ---- predictions = Softmax(logits) per shard (the split listing of Section 3.1.2) -----------------
+
+def test_predictions_hand_example_and_row_sums():
+    # the three-class example above: softmax = (1/6, 1/3, 1/2); shards (2 classes, 1 class)
+    X = np.array([[1.0]]); W = np.array([[0.0], [math.log(2.0)], [math.log(3.0)]])
+    lse = np.array([math.log(6.0)])
+    assert np.allclose(oracle.predictions(X, W[:2], None, lse), [[1 / 6, 1 / 3]], rtol=1e-15)
+    assert np.allclose(oracle.predictions(X, W[2:], None, lse), [[1 / 2]], rtol=1e-15)
+
+
+def test_predictions_concatenate_to_the_softmax():
+    rng = np.random.default_rng(12)
+    B, D, C = 9, 7, 23
+    X = rng.normal(size=(B, D)); W = rng.normal(size=(C, D)); b = rng.normal(size=C)
+    y = rng.integers(0, C, size=B)
+    ref = oracle.unsharded(X, W, b, y, 1.0)
+    shards = [(0, 1), (1, 15), (16, 7)]
+    P = np.concatenate([oracle.predictions(X, W[o:o + c], b[o:o + c], ref["lse"]) for o, c in shards], axis=1)
+    assert np.allclose(P, scipy.special.softmax(oracle.logits(X, W, b), axis=1), rtol=1e-12, atol=1e-15)
+    assert np.allclose(P.sum(axis=1), 1.0, rtol=1e-13)
+    onehot = np.zeros((B, C)); onehot[np.arange(B), y] = 1.0
+    assert np.allclose(P - onehot, ref["dZ"], rtol=1e-12, atol=1e-15)      # dz = softmax - onehot at g = 1
+    # with a shard's own log-sum-exp instead of the combined one the rows would not sum to 1:
+    m, s, _ = oracle.partials(X, W[:16], b[:16], y, 0)
+    own = oracle.predictions(X, W[:16], b[:16], m + np.log(s))
+    assert np.allclose(own.sum(axis=1), 1.0) and not np.allclose(P[:, :16].sum(axis=1), 1.0)
