@@ -203,6 +203,36 @@ def main():
     }
     del blocks, Xg, partials, outs
 
+    # Forward pass of the layer under the paper's two sharding patterns (Section 5.3.2), 8 ways, every
+    # device's share run one after another on this GPU: SP1 = 8 class shards (fwd + combine), SP2 = 8
+    # contraction slices (partial logits over all classes, then the reduction an AllReduce would do).
+    if args.workload == "headline":
+        ways = 8
+        cw, dw_ = C // ways, D // ways
+        m8, s8, t8 = (torch.empty((ways, B), device=dev) for _ in range(3))
+        zparts = [torch.empty((B, C), device=dev) for _ in range(ways)]
+        lse2, loss2 = torch.empty(B, device=dev), torch.empty(B, device=dev)
+
+        def sp1_fwd():
+            for i in range(ways):
+                ws.split_fc_fwd(X, W[i * cw:(i + 1) * cw], None, y, i * cw, m8[i], s8[i], t8[i], work)
+            ws.combine_partials(m8, s8, t8, lse, loss, None)
+
+        def sp2_fwd():
+            for i in range(ways):
+                ws.sp2_partial_logits(X[:, i * dw_:(i + 1) * dw_], W[:, i * dw_:(i + 1) * dw_], zparts[i])
+            ws.sp2_reduce_stats(zparts, None, y, lse2, loss2)
+
+        sp1_us, sp2_us = timed(sp1_fwd, 10), timed(sp2_fwd, 10)
+        result["sharding_patterns_forward"] = {
+            "ways": ways, "sp1_ms": round(sp1_us / 1e3, 4), "sp2_ms": round(sp2_us / 1e3, 4),
+            "sp2_over_sp1": round(sp2_us / sp1_us, 2),
+            "sp2_partial_logit_bytes_written_and_read": 2.0 * ways * B * C * 4,
+            "sp1_exchanged_bytes": 12.0 * ways * B,
+            "max_abs_lse_diff_sp1_vs_sp2": float((lse - lse2).abs().max()),
+        }
+        del zparts
+
     if not args.no_cpu_baseline and args.workload not in first_shard_only:   # one shard of W only: no unsharded oracle
         # The oracle as it stands, on the host cores, on one full step of the same workload
         # (or a row sample of it when the step would take minutes).

@@ -202,6 +202,25 @@ int ws_bridge_fusable(int32_t gather_dim, int32_t n_src, const int64_t* src_exte
                       int32_t partition_dim, int32_t n_dst, const int64_t* dst_extents,
                       int32_t* fusable);
 
+/* ---- The contraction-split sharding pattern, for comparison (Section 3.2.2, Section 5.3.2) --------
+ * The paper's MatMul ShardingUnit has two sharding patterns: SP1 cuts the second input along its
+ * second dimension (the class split every other entry point of this library implements), SP2 cuts
+ * BOTH inputs along the contraction dimension and sums the full-width partial outputs with an
+ * AllReduce; the paper measures SP1 1.6x to 3.75x faster.  These two calls are one device's share
+ * of SP2's forward pass, kept so that the two patterns can be measured side by side:
+ *   ws_sp2_partial_logits   Z_partial[i][c] = sum_{d in slice} X[i][d] * W[c][d]   fp32 [B][ldz], ALL C classes
+ *   ws_sp2_reduce_stats     z = sum_s Z_partial_s (slice order s = 0 .. S-1) + bias;
+ *                           logsumexp[i] = ln sum_c exp(z[i][c]);  loss_rows[i] = logsumexp[i] - z[i][labels[i]]
+ * X_slice bf16 [B][ldx] and W_slice bf16 [C][ldw] hold D_slice (a multiple of 64) columns of X and
+ * W; alignment and size rules as for ws_split_fc_fwd.  Z_partials is a HOST array of S (at most 64)
+ * DEVICE pointers, 16-byte aligned, pitches multiples of 4; bias fp32 [C] 16-byte aligned or NULL. */
+int ws_sp2_partial_logits(const void* X_slice, int64_t ldx, const void* W_slice, int64_t ldw,
+                          int32_t B, int32_t D_slice, int32_t C,
+                          float* Z_partial, int64_t ldz, void* stream);
+int ws_sp2_reduce_stats(const float* const* Z_partials, const int64_t* ldz, int32_t S,
+                        const float* bias, const int32_t* labels, int32_t B, int32_t C,
+                        float* logsumexp, float* loss_rows, void* stream);
+
 /* Optional per-kernel timing, for benchmarks (not part of the paper's method; host-side state,
  * not thread safe).  ws_profile_enable(n) creates a pool of n event pairs (n <= 0 switches
  * timing off and frees the pool); while the pool lasts, every kernel the library launches is

@@ -177,3 +177,22 @@ def predictions(X, W_s, b_s, lse):
     """The shard's columns of Softmax(logits) (the last line of the paper's split listing,
     Section 3.1.2), given the log-sum-exp over ALL classes: P[i, c] = exp(Z_ic - lse_i)."""
     return np.exp(logits(X, W_s, b_s) - _as64(lse)[:, None])
+
+
+def sp2_partial_logits(X, W, d0, d1):
+    """The other sharding pattern of the matmul (Section 3.2.2, SP2): both inputs cut along the
+    contraction; the slice [d0, d1) contributes Z_s[i, c] = sum_{d0 <= d < d1} X[i, d] * W[c, d]
+    for ALL classes."""
+    return _as64(X)[:, d0:d1] @ _as64(W)[:, d0:d1].T
+
+
+def sp2_reduce(Z_parts, b, y):
+    """What the AllReduce of SP2 yields, then the loss: Z = sum_s Z_s + b; (lse, loss) per row."""
+    Z = np.zeros_like(_as64(Z_parts[0]))
+    for Zs in Z_parts:
+        Z = Z + _as64(Zs)
+    if b is not None:
+        Z = Z + _as64(b)[None, :]
+    lse = logsumexp_rows(Z)
+    y = np.asarray(y, dtype=np.int64)
+    return lse, lse - Z[np.arange(Z.shape[0]), y]

@@ -65,11 +65,17 @@ lib.ws_bridge_reduce_partition.argtypes = [ctypes.POINTER(_p), ctypes.POINTER(_i
 lib.ws_bridge_fusable.restype = ctypes.c_int
 lib.ws_bridge_fusable.argtypes = [_i32, _i32, ctypes.POINTER(_i64), _i32, _i32, ctypes.POINTER(_i64), ctypes.POINTER(_i32)]
 
+lib.ws_sp2_partial_logits.restype = ctypes.c_int
+lib.ws_sp2_partial_logits.argtypes = [_p, _i64, _p, _i64, _i32, _i32, _i32, _p, _i64, _p]
+lib.ws_sp2_reduce_stats.restype = ctypes.c_int
+lib.ws_sp2_reduce_stats.argtypes = [ctypes.POINTER(_p), ctypes.POINTER(_i64), _i32, _p, _p, _i32, _i32, _p, _p, _p]
+
 EXPORTS = ["ws_status_string", "ws_version", "ws_fwd_workspace_bytes", "ws_split_fc_fwd",
            "ws_combine_partials", "ws_bwd_workspace_bytes", "ws_split_fc_bwd", "ws_split_fc_predict",
            "ws_profile_enable", "ws_profile_reset", "ws_profile_kernel_count", "ws_profile_kernel_name",
            "ws_profile_read", "ws_balance_widths",
-           "ws_bridge_gather", "ws_bridge_reduce_partition", "ws_bridge_fusable"]
+           "ws_bridge_gather", "ws_bridge_reduce_partition", "ws_bridge_fusable",
+           "ws_sp2_partial_logits", "ws_sp2_reduce_stats"]
 
 
 class WhaleSplitError(RuntimeError):
@@ -223,3 +229,20 @@ def bridge_fusable(gather_dim, src_extents, partition_dim, dst_extents):
     _check(lib.ws_bridge_fusable(int(gather_dim), len(src_extents), a, int(partition_dim), len(dst_extents), b,
                                  ctypes.byref(ok)))
     return bool(ok.value)
+
+
+def sp2_partial_logits(X_slice, W_slice, Z_partial):
+    """Z_partial fp32 [B, C] <- X_slice [B, D_s] . W_slice [C, D_s]^T (column slices may be views)."""
+    B, Ds = X_slice.shape
+    C = W_slice.shape[0]
+    _check(lib.ws_sp2_partial_logits(_ptr(X_slice), X_slice.stride(0), _ptr(W_slice), W_slice.stride(0), B, Ds, C,
+                                     _ptr(Z_partial), Z_partial.stride(0), _stream()))
+
+
+def sp2_reduce_stats(Z_partials, bias, labels, logsumexp, loss_rows):
+    S = len(Z_partials)
+    B, C = Z_partials[0].shape
+    zp = (_p * S)(*[z.data_ptr() for z in Z_partials])
+    zl = (_i64 * S)(*[z.stride(0) for z in Z_partials])
+    _check(lib.ws_sp2_reduce_stats(zp, zl, S, _ptr(bias), _ptr(labels), B, C, _ptr(logsumexp), _ptr(loss_rows),
+                                   _stream()))

@@ -21,7 +21,7 @@ def ws():
 def test_header_symbols_are_exported(ws):
     text = open(os.path.join(ROOT, "include", "whalesplit.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    declared = set(re.findall(r"\b(ws_[a-z_]+)\s*\(", text))
+    declared = set(re.findall(r"\b(ws_[a-z0-9_]+)\s*\(", text))
     assert declared == set(ws.EXPORTS)
     for name in declared:
         assert getattr(ws.lib, name) is not None
@@ -109,3 +109,25 @@ def test_predict_argument_validation(ws):
     assert pred(C=9, ldp=12) == E["WS_ERR_ALIGN"]                 # pitch not a multiple of 8
     assert pred(P=A + 2) == E["WS_ERR_ALIGN"] and pred(lse=A + 2) == E["WS_ERR_ALIGN"]
     assert pred(B=1 << 20, ldx=4096) == E["WS_ERR_SHAPE"]         # X beyond 32-bit offsets
+
+
+def test_sp2_argument_validation(ws):
+    E = {ws.status_string(i): i for i in range(7)}
+
+    def part(X=A, ldx=64, W=A, ldw=64, B=4, Ds=64, C=8, Z=A, ldz=8):
+        return ws.lib.ws_sp2_partial_logits(X, ldx, W, ldw, B, Ds, C, Z, ldz, None)
+
+    assert part(Z=None) == E["WS_ERR_NULL"]
+    assert part(Ds=32) == E["WS_ERR_SHAPE"] and part(ldz=7) == E["WS_ERR_SHAPE"] and part(ldx=32) == E["WS_ERR_SHAPE"]
+    assert part(X=A + 8) == E["WS_ERR_ALIGN"] and part(ldw=68) == E["WS_ERR_ALIGN"] and part(Z=A + 2) == E["WS_ERR_ALIGN"]
+
+    def red(parts=(A, A), lds=(8, 8), S=None, bias=None, y=A, B=4, C=8, lse=A, loss=A):
+        P = (ctypes.c_void_p * len(parts))(*parts)
+        L = (ctypes.c_int64 * len(parts))(*lds)
+        return ws.lib.ws_sp2_reduce_stats(P, L, len(parts) if S is None else S, bias, y, B, C, lse, loss, None)
+
+    assert red(y=None) == E["WS_ERR_NULL"] and red(parts=(A, None)) == E["WS_ERR_NULL"]
+    assert red(S=0) == E["WS_ERR_RANGE"] and red(parts=(A,) * 65, lds=(8,) * 65) == E["WS_ERR_RANGE"]
+    assert red(C=0) == E["WS_ERR_SHAPE"] and red(lds=(8, 4)) == E["WS_ERR_SHAPE"]
+    assert red(parts=(A, A + 4)) == E["WS_ERR_ALIGN"] and red(lds=(8, 10)) == E["WS_ERR_ALIGN"]
+    assert red(bias=A + 4) == E["WS_ERR_ALIGN"]

@@ -297,3 +297,28 @@ def test_predictions_concatenate_to_the_softmax():
     m, s, _ = oracle.partials(X, W[:16], b[:16], y, 0)
     own = oracle.predictions(X, W[:16], b[:16], m + np.log(s))
     assert np.allclose(own.sum(axis=1), 1.0) and not np.allclose(P[:, :16].sum(axis=1), 1.0)
+
+
+# ---- the contraction-split sharding pattern (SP2 of Section 3.2.2) -------------------------------
+
+def test_sp2_hand_example():
+    X = np.array([[1.0, 2.0]]); W = np.array([[3.0, 4.0], [5.0, 6.0]])
+    assert oracle.sp2_partial_logits(X, W, 0, 1).tolist() == [[3.0, 5.0]]
+    assert oracle.sp2_partial_logits(X, W, 1, 2).tolist() == [[8.0, 12.0]]      # sum = X . W^T = (11, 17)
+    lse, loss = oracle.sp2_reduce([np.array([[3.0, 5.0]]), np.array([[8.0, 12.0]])], None, [1])
+    assert abs(lse[0] - (17.0 + math.log1p(math.exp(-6.0)))) < 1e-14
+    assert abs(loss[0] - math.log1p(math.exp(-6.0))) < 1e-14
+
+
+def test_sp2_partials_sum_to_the_logits_and_give_the_same_loss():
+    rng = np.random.default_rng(14)
+    B, D, C = 7, 12, 19
+    X = rng.normal(size=(B, D)); W = rng.normal(size=(C, D)); b = rng.normal(size=C)
+    y = rng.integers(0, C, size=B)
+    ref = oracle.unsharded(X, W, b, y, 1.0)
+    for cuts in ([0, 12], [0, 1, 12], [0, 4, 8, 12], list(range(13))):
+        parts = [oracle.sp2_partial_logits(X, W, a, e) for a, e in zip(cuts[:-1], cuts[1:])]
+        assert all(p.shape == (B, C) for p in parts)          # every slice yields ALL classes
+        assert np.allclose(sum(parts), oracle.logits(X, W, None), rtol=1e-12, atol=1e-13)
+        lse, loss = oracle.sp2_reduce(parts, b, y)
+        assert np.allclose(lse, ref["lse"], rtol=1e-13) and np.allclose(loss, ref["loss"], rtol=1e-11, atol=1e-13)
