@@ -48,6 +48,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="headline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the measurements outside the timed step (bridge ends, SP1 vs SP2 forward)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (a kernel of known traffic for scaling "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -169,8 +171,17 @@ def main():
         "kernels": kernels,
     }
 
-    # The bridge-layer ends at this workload's shape (8 replicas feed X; 8 shards' dX_partial go back):
-    # HBM-bound copy / add kernels, timed with events on the launch stream, outside the step above.
+    if not args.no_extras:
+        measure_extras(args, result, ws, torch, dev, X, W, y, B, D, C, work, lse, loss)
+
+    if not args.no_cpu_baseline and args.workload not in first_shard_only:   # one shard of W only: no unsharded oracle
+        cpu_baseline(args, result, inputs, p, B, D, C, lse)
+    print(json.dumps(result), flush=True)
+
+
+def measure_extras(args, result, ws, torch, dev, X, W, y, B, D, C, work, lse, loss):
+    """Measurements outside the timed step.  The bridge-layer ends at this workload's shape (8 replicas feed X;
+    8 shards' dX_partial go back): HBM-bound copy / add kernels, timed with events on the launch stream."""
     R = 8 if B % 8 == 0 else 1
     blocks = [X[i * (B // R):(i + 1) * (B // R)].clone() for i in range(R)]
     Xg = torch.empty_like(X)
@@ -211,12 +222,13 @@ def main():
         cw, dw_ = C // ways, D // ways
         m8, s8, t8 = (torch.empty((ways, B), device=dev) for _ in range(3))
         zparts = [torch.empty((B, C), device=dev) for _ in range(ways)]
+        lse1, loss1 = torch.empty(B, device=dev), torch.empty(B, device=dev)
         lse2, loss2 = torch.empty(B, device=dev), torch.empty(B, device=dev)
 
         def sp1_fwd():
             for i in range(ways):
                 ws.split_fc_fwd(X, W[i * cw:(i + 1) * cw], None, y, i * cw, m8[i], s8[i], t8[i], work)
-            ws.combine_partials(m8, s8, t8, lse, loss, None)
+            ws.combine_partials(m8, s8, t8, lse1, loss1, None)
 
         def sp2_fwd():
             for i in range(ways):
@@ -229,35 +241,37 @@ def main():
             "sp2_over_sp1": round(sp2_us / sp1_us, 2),
             "sp2_partial_logit_bytes_written_and_read": 2.0 * ways * B * C * 4,
             "sp1_exchanged_bytes": 12.0 * ways * B,
-            "max_abs_lse_diff_sp1_vs_sp2": float((lse - lse2).abs().max()),
+            "max_abs_lse_diff_sp1_vs_sp2": float((lse1 - lse2).abs().max()),
+            "max_abs_lse_diff_sp1_vs_one_shard": float((lse1 - lse).abs().max()),
         }
         del zparts
 
-    if not args.no_cpu_baseline and args.workload not in first_shard_only:   # one shard of W only: no unsharded oracle
-        # The oracle as it stands, on the host cores, on one full step of the same workload
-        # (or a row sample of it when the step would take minutes).
-        from oracle import oracle
-        try:
-            from threadpoolctl import threadpool_info
-            cores = max([d.get("num_threads", 1) for d in threadpool_info()] or [1])
-        except Exception:
-            cores = os.cpu_count()
-        rows = B if 6.0 * B * D * C <= 2.0e12 else max(1, int(2.0e12 / (6.0 * D * C)))
-        Xo = inputs.bf16_bits_to_f64(p.X_bits[:rows])
-        Wo = inputs.bf16_bits_to_f64(p.W_bits)
-        t0 = time.perf_counter()
-        ref = oracle.unsharded(Xo, Wo, None, p.labels[:rows], 1.0)
-        dt = time.perf_counter() - t0
-        result["cpu_baseline"] = {
-            "value": round(rows / dt, 2),
-            "unit": "samples/s",
-            "cores": int(cores),
-            "kind": "oracle",
-            "sample": f"one fwd+bwd step of the fp64 numpy oracle on {rows} of {B} rows, all {C} classes, {dt:.1f} s",
-        }
-        got = lse.cpu().numpy()[:rows]
-        result["cpu_baseline"]["max_abs_lse_diff_vs_gpu"] = float(np.max(np.abs(got - ref["lse"])))
-    print(json.dumps(result), flush=True)
+
+def cpu_baseline(args, result, inputs, p, B, D, C, lse):
+    """The oracle as it stands, on the host cores, on one full step of the same workload (or a row
+    sample of it when the step would take minutes)."""
+    import numpy as np
+    from oracle import oracle
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([d.get("num_threads", 1) for d in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count()
+    rows = B if 6.0 * B * D * C <= 2.0e12 else max(1, int(2.0e12 / (6.0 * D * C)))
+    Xo = inputs.bf16_bits_to_f64(p.X_bits[:rows])
+    Wo = inputs.bf16_bits_to_f64(p.W_bits)
+    t0 = time.perf_counter()
+    ref = oracle.unsharded(Xo, Wo, None, p.labels[:rows], 1.0)
+    dt = time.perf_counter() - t0
+    result["cpu_baseline"] = {
+        "value": round(rows / dt, 2),
+        "unit": "samples/s",
+        "cores": int(cores),
+        "kind": "oracle",
+        "sample": f"one fwd+bwd step of the fp64 numpy oracle on {rows} of {B} rows, all {C} classes, {dt:.1f} s",
+    }
+    got = lse.cpu().numpy()[:rows]
+    result["cpu_baseline"]["max_abs_lse_diff_vs_gpu"] = float(np.max(np.abs(got - ref["lse"])))
 
 
 if __name__ == "__main__":
