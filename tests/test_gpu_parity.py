@@ -44,6 +44,8 @@ def test_cfg1_tiny(H):
     (300, 256, [500, 700, 77]),
     (257, 64, [255, 257, 256]),
     (513, 128, [1030]),
+    (300, 4096, [600]),
+    (5000, 64, [40, 7]),
 ])
 def test_ragged_shapes_with_bias(H, B, D, widths):
     """Row counts and shard widths that are not multiples of any tile, several tiles wide, with a
