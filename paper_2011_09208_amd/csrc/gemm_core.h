@@ -321,6 +321,97 @@ __device__ __forceinline__ void zero_acc(acc_t& acc) {
             for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.0f;
 }
 
+// ---- thin tiles ------------------------------------------------------------------------------------
+// A launch whose tile count is not a multiple of the 256 compute units ends with a round in which
+// most of them idle.  The tiles of that last round can instead be cut into four "thin" tiles of
+// 256 x 64 (one wave column of a full tile each) and handed to four times as many workgroups.  A thin
+// tile does a quarter of the MFMA work for 5/8 of the staging traffic, so it runs at the pace of its
+// LDS writes, about a quarter to a third of a full tile's time.  Both operands are KC.
+constexpr int THIN_N = WAVE_N;                         // 64 columns
+constexpr int THIN_WAVE_M = TILE_M / 8;                // a wave of a thin tile: 32 rows x 64 columns
+constexpr int THIN_MT = THIN_WAVE_M / 16, THIN_NT = THIN_N / 16;
+constexpr int THIN_STAGE_BYTES = OPERAND_TILE_BYTES + THIN_N * TILE_K * 2;    // 32 KiB A + 8 KiB B
+typedef f32x4 thin_acc_t[THIN_MT][THIN_NT];
+
+// acc[mt][nt] += A(m0 .. m0+255, k) * B(n0 .. n0+63, k) for k in [k_begin, k_begin + 64 * k_steps);
+// wave w holds rows 32 w .. 32 w + 31.  Two LDS stages, the same software pipeline as the full tile in
+// two slots of 8 MFMAs per k-step: slot A multiplies k-substep 0 while the fragments of substep 1 are
+// read, the next k-step goes registers -> LDS and the one after it global -> registers; after the
+// barrier slot B multiplies substep 1 while the first fragments of the next k-step are read.
+// k-steps beyond the last are clamped to the last one (a harmless reload).  Ends with a workgroup barrier.
+__device__ __forceinline__ void thin_mainloop(thin_acc_t& acc, const Operand& A, const Operand& Bop, int m0, int n0,
+                                              int k_begin, int k_steps, char* lds) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    FragAddr<KC, THIN_MT> fa;
+    FragAddr<KC, THIN_NT> fb;
+    fa.init(lane, wave * THIN_WAVE_M);
+    fb.init(lane, 0);
+    const uint32_t a_off = tile_lane_offset<KC>(A, m0, tid);
+    const uint32_t b_off = tile_lane_offset<KC>(Bop, n0, tid);       // thread t: row t / 8 of the 64, chunk t % 8
+    const int last = k_steps - 1;
+    constexpr int NM = THIN_MT * THIN_NT, NR = THIN_MT + THIN_NT;
+    u32x4 ra[4], rb;
+    bf16x8 af[2][THIN_MT], bfr[2][THIN_NT];
+    auto g2r = [&](int step) {
+        const int k0 = k_begin + (step < last ? step : last) * TILE_K;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) ra[q] = quarter_g2r<KC>(A, a_off, k0, q);
+        rb = quarter_g2r<KC>(Bop, b_off, k0, 0);
+    };
+    auto r2s = [&](char* stage) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) quarter_r2s<KC>(stage, ra[q], tid, q);
+        quarter_r2s<KC>(stage + OPERAND_TILE_BYTES, rb, tid, 0);
+    };
+    auto frags = [&](int set, const char* stage, int s) {
+#pragma unroll
+        for (int i = 0; i < THIN_MT; ++i) af[set][i] = fa.load(stage, i, s);
+#pragma unroll
+        for (int i = 0; i < THIN_NT; ++i) bfr[set][i] = fb.load(stage + OPERAND_TILE_BYTES, i, s);
+    };
+    auto mfmas = [&](int set) {
+#pragma unroll
+        for (int i = 0; i < THIN_MT; ++i)
+#pragma unroll
+            for (int jn = 0; jn < THIN_NT; ++jn)
+                acc[i][jn] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[set][i], bfr[set][jn], acc[i][jn], 0, 0, 0);
+    };
+    g2r(0);
+    r2s(lds);
+    g2r(1);
+    __syncthreads();
+    frags(0, lds, 0);
+    for (int j = 0; j < last; ++j) {
+        const char* cur = lds + (j & 1) * THIN_STAGE_BYTES;
+        char* nxt = lds + ((j + 1) & 1) * THIN_STAGE_BYTES;
+        frags(1, cur, 1);
+        mfmas(0);
+        r2s(nxt);                  // free since the barrier of the iteration before
+        g2r(j + 2);
+        SlotSched<0, NM, NR, 5, 5>::apply();
+        __syncthreads();
+        frags(0, nxt, 0);
+        mfmas(1);
+        SlotSched<0, NM, NR, 0, 0>::apply();
+    }
+    {
+        const char* cur = lds + (last & 1) * THIN_STAGE_BYTES;
+        frags(1, cur, 1);
+        mfmas(0);
+        SlotSched<0, NM, NR, 0, 0>::apply();
+        mfmas(1);
+    }
+    __syncthreads();
+}
+
+// How a launch of n_tiles full tiles is cut: the tiles of the last, partial round become thin tiles
+// when that round would leave at least half of the compute units idle.
+struct TilePlan {
+    int n_full;      // full tiles, logical ids 0 .. n_full - 1 (workgroups 0 .. 8 * ceil(n_full / 8) - 1)
+    int n_thin;      // thin tiles: 4 per remaining full tile, workgroups thin_first .. thin_first + n_thin - 1
+    int thin_first;
+};
+
 // Workgroups are handed to the 8 XCDs round-robin by their linear id; each XCD has its own L2.
 // Map the hardware id to a logical tile id so that each XCD walks one contiguous range of
 // logical tiles (tiles that share an operand panel are numbered next to each other).

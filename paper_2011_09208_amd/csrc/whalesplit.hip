@@ -73,7 +73,31 @@ struct FcArgs {
     int B, D, C, class_offset;
     int Bpad;        // B rounded up to 256
     int nBT, nCT;    // tiles along the batch and class dimensions
+    TilePlan plan;   // which of the nBT * nCT tiles run as full tiles and which as four thin tiles each
 };
+
+// The tile a workgroup of a logits kernel works on: full (piece < 0) or thin piece 0 .. 3 of it.
+struct TileRef {
+    int ct, bt, piece;
+    bool valid;
+};
+
+__device__ __forceinline__ TileRef logits_tile_ref(const FcArgs& a) {
+    TileRef r;
+    r.piece = -1;
+    int tile;
+    if ((int)blockIdx.x >= a.plan.thin_first) {
+        const int q = (int)blockIdx.x - a.plan.thin_first;
+        tile = q < a.plan.n_thin ? a.plan.n_full + (q >> 2) : -1;
+        r.piece = q & 3;
+    } else {
+        tile = xcd_logical_tile(a.plan.n_full);
+    }
+    r.valid = tile >= 0;
+    r.ct = tile / a.nBT;       // batch tiles fastest: neighbours share the W panel
+    r.bt = tile % a.nBT;
+    return r;
+}
 
 // Runs the logits GEMM of one 256-class x 256-row tile and leaves z (bias added, padding = -inf)
 // in acc.  M = classes (A = W_s, KC), N = batch rows (B operand = X, KC), K = D.
@@ -96,6 +120,107 @@ __device__ __forceinline__ void logits_tile(acc_t& acc, const FcArgs& a, int ct,
     add_bias_and_mask(acc, sbias, has_bias, wm * WAVE_M, a.C - (ct * TILE_M + wm * WAVE_M), (tid & 63) >> 4);
 }
 
+// Class id (relative to the wave's first class) of accumulator register v of M-tile mt in a thin tile
+// is the same expression, with two M-tiles per wave instead of eight.
+//
+// z of thin tile `piece` (rows 64 * piece .. + 63 of batch tile bt), bias added, padding = -inf.
+__device__ __forceinline__ void logits_thin(thin_acc_t& acc, const FcArgs& a, int ct, int bt, int piece, char* lds,
+                                            float* sbias) {
+#pragma unroll
+    for (int i = 0; i < THIN_MT; ++i)
+#pragma unroll
+        for (int j = 0; j < THIN_NT; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const Operand A = make_operand(a.W, a.ldw, a.C, a.D);
+    const Operand Bo = make_operand(a.X, a.ldx, a.B, a.D);
+    thin_mainloop(acc, A, Bo, ct * TILE_M, bt * TILE_N + piece * THIN_N, 0, a.D / TILE_K, lds);
+    const int tid = threadIdx.x, wave = tid >> 6, g = (tid & 63) >> 4;
+    if (a.bias != nullptr) {
+        if (tid < TILE_M) {
+            const int c = ct * TILE_M + tid;
+            sbias[tid] = c < a.C ? a.bias[c] : 0.0f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int mt = 0; mt < THIN_MT; ++mt) {
+            const f32x4 b4 = *reinterpret_cast<const f32x4*>(sbias + wave * THIN_WAVE_M + 16 * mt + 4 * g);
+#pragma unroll
+            for (int nt = 0; nt < THIN_NT; ++nt) acc[mt][nt] += b4;
+        }
+    }
+    const int c_left = a.C - (ct * TILE_M + wave * THIN_WAVE_M);
+    if (c_left < THIN_WAVE_M) {
+#pragma unroll
+        for (int mt = 0; mt < THIN_MT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                if (acc_row(mt, v, g) >= c_left) {
+#pragma unroll
+                    for (int nt = 0; nt < THIN_NT; ++nt) acc[mt][nt][v] = NEG_INF;
+                }
+    }
+}
+
+// Forward statistics of a thin tile: every wave reduces its 32 classes per row, the eight waves'
+// pairs are merged through LDS in wave order.
+__device__ __forceinline__ void fwd_stats_thin(const FcArgs& a, const TileRef& r, char* lds,
+                                               float* __restrict__ part_max, float* __restrict__ part_sum,
+                                               float* __restrict__ label_logit) {
+    float* sbias = reinterpret_cast<float*>(lds);
+    float* red_m = sbias + 256;            // [8][64]
+    float* red_s = red_m + 512;
+    thin_acc_t acc;
+    logits_thin(acc, a, r.ct, r.bt, r.piece, lds, sbias);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 4, jl = lane & 15;
+    const int cw0 = r.ct * TILE_M + wave * THIN_WAVE_M;
+    const int row0 = r.bt * TILE_N + r.piece * THIN_N;
+#pragma unroll
+    for (int nt = 0; nt < THIN_NT; ++nt) {
+        const int row = row0 + 16 * nt + jl;
+        float mx = NEG_INF;
+#pragma unroll
+        for (int mt = 0; mt < THIN_MT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) mx = fmaxf(mx, acc[mt][nt][v]);
+        const float ms = (mx == NEG_INF) ? 0.0f : mx;
+        const float shift = -ms * LOG2E;
+        float s = 0.0f;
+#pragma unroll
+        for (int mt = 0; mt < THIN_MT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) s += __builtin_amdgcn_exp2f(fmaf(acc[mt][nt][v], LOG2E, shift));
+        merge_ms(mx, s, lane_xor(mx, 16), lane_xor(s, 16));
+        merge_ms(mx, s, lane_xor(mx, 32), lane_xor(s, 32));
+        if (g == 0) {
+            red_m[wave * THIN_N + 16 * nt + jl] = mx;
+            red_s[wave * THIN_N + 16 * nt + jl] = s;
+        }
+        const bool row_ok = row < a.B;
+        const int local = row_ok ? a.labels[row] - a.class_offset : -1;
+        const bool in_shard = local >= 0 && local < a.C;
+        const int rel = local - cw0;
+        const bool mine = in_shard && rel >= 0 && rel < THIN_WAVE_M && ((rel & 15) >> 2) == g;
+        if (__any(mine)) {
+            float t = 0.0f;
+#pragma unroll
+            for (int mt = 0; mt < THIN_MT; ++mt)
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    if (acc_row(mt, v, g) == rel) t = acc[mt][nt][v];
+            if (mine) label_logit[row] = t;
+        }
+        if (r.ct == 0 && wave == 0 && g == 0 && row_ok && !in_shard) label_logit[row] = 0.0f;
+    }
+    __syncthreads();
+    if (tid < THIN_N) {
+        float m = red_m[tid], s = red_s[tid];
+#pragma unroll
+        for (int w = 1; w < 8; ++w) merge_ms(m, s, red_m[w * THIN_N + tid], red_s[w * THIN_N + tid]);
+        const int64_t o = (int64_t)r.ct * a.Bpad + row0 + tid;
+        part_max[o] = m;
+        part_sum[o] = s;
+    }
+}
+
 __global__ __launch_bounds__(NTHREADS) void fwd_logits_stats(FcArgs a, float* __restrict__ part_max,
                                                               float* __restrict__ part_sum,
                                                               float* __restrict__ label_logit) {
@@ -103,9 +228,13 @@ __global__ __launch_bounds__(NTHREADS) void fwd_logits_stats(FcArgs a, float* __
     float* sbias = reinterpret_cast<float*>(lds);          // reused after the main loop
     float* red_m = reinterpret_cast<float*>(lds) + 256;    // [2][256]
     float* red_s = red_m + 512;
-    const int tile = xcd_logical_tile(a.nBT * a.nCT);
-    if (tile < 0) return;
-    const int ct = tile / a.nBT, bt = tile % a.nBT;   // batch tiles fastest: neighbours share the W panel
+    const TileRef ref = logits_tile_ref(a);
+    if (!ref.valid) return;
+    if (ref.piece >= 0) {
+        fwd_stats_thin(a, ref, lds, part_max, part_sum, label_logit);
+        return;
+    }
+    const int ct = ref.ct, bt = ref.bt;
 
     acc_t acc;
     logits_tile(acc, a, ct, bt, lds, sbias);
@@ -256,6 +385,86 @@ __device__ __forceinline__ void transpose_x_tiles(const FcArgs& a, const XtArgs&
     }
 }
 
+// dz of a thin tile: the same steps as in bwd_recompute_dz below on a 256-class x 64-row tile.  Its
+// column sums are one db partial, in the slot the matching wave column of a full tile would fill.
+__device__ __forceinline__ void dz_thin(const FcArgs& a, const TileRef& r, char* lds,
+                                        const float* __restrict__ logsumexp, float grad_scale,
+                                        uint16_t* __restrict__ dZ, int64_t ldz, float* __restrict__ db_part) {
+    float* sbias = reinterpret_cast<float*>(lds);
+    thin_acc_t acc;
+    logits_thin(acc, a, r.ct, r.bt, r.piece, lds, sbias);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 4, jl = lane & 15;
+    const int cw0 = r.ct * TILE_M + wave * THIN_WAVE_M;
+    const int row0 = r.bt * TILE_N + r.piece * THIN_N;
+#pragma unroll
+    for (int nt = 0; nt < THIN_NT; ++nt) {
+        const int row = row0 + 16 * nt + jl;
+        const bool row_ok = row < a.B;
+        const float lse = row_ok ? logsumexp[row] : 0.0f;
+        const float gs = row_ok ? grad_scale : 0.0f;
+        const float shift = __log2f(fabsf(gs)) - lse * LOG2E;
+#pragma unroll
+        for (int mt = 0; mt < THIN_MT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[mt][nt][v] = __builtin_amdgcn_exp2f(fmaf(acc[mt][nt][v], LOG2E, shift));
+        if (grad_scale < 0.0f) {
+#pragma unroll
+            for (int mt = 0; mt < THIN_MT; ++mt) acc[mt][nt] = -acc[mt][nt];
+        }
+        const int local = row_ok ? a.labels[row] - a.class_offset : -1;
+        const bool in_shard = local >= 0 && local < a.C;
+        const int rel = local - cw0;
+        const bool mine = in_shard && rel >= 0 && rel < THIN_WAVE_M && ((rel & 15) >> 2) == g;
+        if (__any(mine)) {
+#pragma unroll
+            for (int mt = 0; mt < THIN_MT; ++mt)
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    if (mine && acc_row(mt, v, g) == rel) acc[mt][nt][v] -= gs;
+        }
+    }
+    if (db_part != nullptr) {
+        // a lane adds its four N-tiles; the 16 lanes with the same classes reduce-scatter the 8 sums in
+        // three exchange steps and add the last pair, so lanes 2 i and 2 i + 1 both hold sum i
+        float val[4 * THIN_MT];
+#pragma unroll
+        for (int mt = 0; mt < THIN_MT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                val[4 * mt + v] = (acc[mt][0][v] + acc[mt][1][v]) + (acc[mt][2][v] + acc[mt][3][v]);
+#pragma unroll
+        for (int step = 0; step < 3; ++step) {
+            const int h = (2 * THIN_MT) >> step, mask = 8 >> step;
+            const bool up = (jl & mask) != 0;
+#pragma unroll
+            for (int i = 0; i < h; ++i) {
+                const float keep = up ? val[i + h] : val[i];
+                const float send = up ? val[i] : val[i + h];
+                val[i] = keep + lane_xor(send, mask);
+            }
+        }
+        val[0] += lane_xor(val[0], 1);
+        if ((jl & 1) == 0) {
+            const int i = jl >> 1;                      // accumulator row index 4 * mt + v
+            db_part[(int64_t)(4 * r.bt + r.piece) * ldz + cw0 + 16 * (i >> 2) + 4 * g + (i & 3)] = val[0];
+        }
+    }
+    __syncthreads();                       // the bias staging area is about to be overwritten
+#pragma unroll
+    for (int nt = 0; nt < THIN_NT; ++nt) {
+        const int n = 16 * nt + jl;
+#pragma unroll
+        for (int mt = 0; mt < THIN_MT; ++mt) {
+            u32x2 pk;
+            pk[0] = pack_bf16(acc[mt][nt][0], acc[mt][nt][1]);
+            pk[1] = pack_bf16(acc[mt][nt][2], acc[mt][nt][3]);
+            *reinterpret_cast<u32x2*>(lds + out_tile_offset(n, wave * THIN_WAVE_M + 16 * mt + 4 * g)) = pk;
+        }
+    }
+    __syncthreads();
+    lds_tile_store_rows(lds, dZ + (int64_t)row0 * ldz + r.ct * TILE_M, ldz, THIN_N, TILE_M);
+}
+
 __global__ __launch_bounds__(NTHREADS) void bwd_recompute_dz(FcArgs a, const float* __restrict__ logsumexp,
                                                               float grad_scale, uint16_t* __restrict__ dZ,
                                                               int64_t ldz, float* __restrict__ db_part,
@@ -266,9 +475,13 @@ __global__ __launch_bounds__(NTHREADS) void bwd_recompute_dz(FcArgs a, const flo
         transpose_x_tiles(a, xt, (int)blockIdx.x - xt.first_block, lds);
         return;
     }
-    const int tile = xcd_logical_tile(a.nBT * a.nCT);
-    if (tile < 0) return;
-    const int ct = tile / a.nBT, bt = tile % a.nBT;
+    const TileRef ref = logits_tile_ref(a);
+    if (!ref.valid) return;
+    if (ref.piece >= 0) {
+        dz_thin(a, ref, lds, logsumexp, grad_scale, dZ, ldz, db_part);
+        return;
+    }
+    const int ct = ref.ct, bt = ref.bt;
 
     acc_t acc;
     logits_tile(acc, a, ct, bt, lds, sbias);
@@ -506,6 +719,18 @@ __global__ __launch_bounds__(NTHREADS) void bwd_dw(DwArgs a, FinishArgs fin) {
 static inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 static inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 static inline int xcd_grid(int n_tiles) { return 8 * ((n_tiles + 7) / 8); }
+
+// Full tiles fill whole rounds of the 256 compute units; a last round that would leave half of them or
+// more idle is run as thin tiles (four per full tile) instead.
+static TilePlan plan_tiles(int n_tiles, bool allow_thin) {
+    TilePlan t;
+    const int tail = n_tiles % 256;
+    const bool thin = allow_thin && tail > 0 && tail <= 128;
+    t.n_full = thin ? n_tiles - tail : n_tiles;
+    t.n_thin = thin ? 4 * tail : 0;
+    t.thin_first = xcd_grid(t.n_full);
+    return t;
+}
 // Workgroups appended to a GEMM launch for its small side job (X^T, the final reductions).
 static const int SIDE_BLOCKS = 128;
 
@@ -650,7 +875,8 @@ int ws_split_fc_fwd(const void* X, int64_t ldx, const void* W_shard, int64_t ldw
     float* part_max = static_cast<float*>(workspace);
     float* part_sum = part_max + (size_t)a.nCT * a.Bpad;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    WS_LAUNCH(KID_FWD, fwd_logits_stats, dim3(xcd_grid(a.nBT * a.nCT)), dim3(NTHREADS), s, a, part_max,
+    a.plan = plan_tiles(a.nBT * a.nCT, true);
+    WS_LAUNCH(KID_FWD, fwd_logits_stats, dim3(a.plan.thin_first + a.plan.n_thin), dim3(NTHREADS), s, a, part_max,
                        part_sum, label_logit);
     WS_LAUNCH(KID_MERGE, merge_class_tiles, dim3((B + 15) / 16), dim3(1024), s, part_max, part_sum, a.nCT,
                        a.Bpad, B, row_max, row_sumexp);
@@ -704,7 +930,8 @@ int ws_split_fc_bwd(const void* X, int64_t ldx, const void* W_shard, int64_t ldw
     a.Bpad = (int)p.Bpad; a.nBT = p.nBT; a.nCT = p.nCT;
     XtArgs xt;
     xt.XT = XT; xt.ldxt = p.Bpad;
-    xt.first_block = xcd_grid(p.nBT * p.nCT);
+    a.plan = plan_tiles(p.nBT * p.nCT, true);
+    xt.first_block = a.plan.thin_first + a.plan.n_thin;
     xt.n_blocks = (int)std::min<int64_t>((p.Bpad / 64) * (D / 64), SIDE_BLOCKS);
     WS_LAUNCH(KID_DZ, bwd_recompute_dz, dim3(xt.first_block + xt.n_blocks), dim3(NTHREADS), s, a, logsumexp,
               grad_scale, dZ, p.Cpad, db_shard ? db_part : nullptr, xt);
@@ -752,6 +979,7 @@ int ws_split_fc_predict(const void* X, int64_t ldx, const void* W_shard, int64_t
     a.Bpad = (int)round_up(B, 256);
     a.nBT = a.Bpad / 256;
     a.nCT = (int)(round_up(C_shard, 256) / 256);
+    a.plan = plan_tiles(a.nBT * a.nCT, false);
     hipStream_t s = static_cast<hipStream_t>(stream);
     WS_LAUNCH(KID_PREDICT, predict_probs, dim3(xcd_grid(a.nBT * a.nCT)), dim3(NTHREADS), s, a, logsumexp,
               static_cast<uint16_t*>(P), ldp);
