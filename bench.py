@@ -44,8 +44,8 @@ def read_traffic(workload):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="headline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
@@ -119,11 +119,15 @@ def main():
     ws.profile_enable(args.steps * (7 * S + 2) + 16)
     ws.profile_reset()
     torch.cuda.synchronize()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for i in range(args.steps):
+        marks[i].record()
         step()
+    marks[args.steps].record()
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
     prof = ws.profile_read()
     ws.profile_enable(0)
 
@@ -137,6 +141,13 @@ def main():
     dominant = max(GEMM_KERNELS, key=lambda k: kernels[k]["avg_ms"])
     for k in GEMM_KERNELS:
         kernels[k]["tflops"] = round(flops_per_launch / (kernels[k]["avg_ms"] * 1e-3) / 1e12, 2)
+    # the two reduction kernels of the forward path move a few MB: HBM GB/s from their algorithmic bytes
+    n_ct = -(-(c_total // S) // 256)
+    small_bytes = {"merge_class_tiles": 8.0 * n_ct * (-(-B // 256) * 256) + 8.0 * B,
+                   "combine_partials": 12.0 * S * B + 8.0 * B}
+    for k, nbytes_k in small_bytes.items():
+        if k in kernels:
+            kernels[k]["GB/s"] = round(nbytes_k / (kernels[k]["avg_ms"] * 1e-3) / 1e9, 1)
     achieved = kernels[dominant]["tflops"]
     traffic = read_traffic(args.workload).get(dominant)
     credited = 6.0 * B * D * c_total
@@ -178,6 +189,8 @@ def main():
         "pct_bf16_mfma_peak_credited_6BDC": round(100.0 * credited / (ms_per_step * 1e-3) / (BF16_DENSE_PEAK_TFLOPS * 1e12), 2),
         "pct_bf16_mfma_peak_executed_8BDC": round(100.0 * credited * 8 / 6 / (ms_per_step * 1e-3) / (BF16_DENSE_PEAK_TFLOPS * 1e12), 2),
         "ms_per_step_without_event_records": round(plain_ms, 4),
+        "ms_per_step_median": round(per_step[len(per_step) // 2], 4),
+        "ms_per_step_min": round(per_step[0], 4),
         "roofline": roofline,
         "kernels": kernels,
     }
