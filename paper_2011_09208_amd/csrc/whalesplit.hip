@@ -12,6 +12,8 @@
 //   bwd_dx             dX_partial = dz . W_s, split along the class contraction; partial sums
 //   bwd_dw             dW_s = dz^T . X; its surplus workgroups sum the split-K partials of dX
 //                      (optionally accumulating into the caller's dX) and the db partials
+// fwd_logits_stats and bwd_recompute_dz run the tiles of a ragged last round (256 compute units) as
+// four thin 256 x 64 tiles each (logits_thin, fwd_stats_thin, dz_thin; plan_tiles on the host).
 #include <hip/hip_runtime.h>
 #include <algorithm>
 #include <limits.h>
