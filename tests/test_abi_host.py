@@ -131,3 +131,10 @@ def test_sp2_argument_validation(ws):
     assert red(C=0) == E["WS_ERR_SHAPE"] and red(lds=(8, 4)) == E["WS_ERR_SHAPE"]
     assert red(parts=(A, A + 4)) == E["WS_ERR_ALIGN"] and red(lds=(8, 10)) == E["WS_ERR_ALIGN"]
     assert red(bias=A + 4) == E["WS_ERR_ALIGN"]
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert res.returncode != 0 and "ONE GPU" in (res.stderr + res.stdout)
