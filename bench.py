@@ -238,6 +238,17 @@ def measure_extras(args, result, ws, torch, dev, X, W, y, B, D, C, work, lse, lo
     }
     del blocks, Xg, partials, outs
 
+    # The backward call with the SGD update folded in (W and dW are both bf16: same bytes written, W read
+    # once more), against the plain one, on the timed workload's first shard.  lr = 0 keeps W as it is.
+    if work.numel() >= ws.bwd_workspace_bytes(B, D, W.shape[0]):       # single-shard workloads
+        dXs = torch.empty((B, D), device=dev)
+        dWs = torch.empty((W.shape[0], D), device=dev, dtype=torch.bfloat16)
+        plain_us = timed(lambda: ws.split_fc_bwd(X, W, None, lse, y, 0, 1.0, dXs, False, dWs, None, work), 10)
+        fused_us = timed(lambda: ws.split_fc_bwd_sgd(X, W, None, lse, y, 0, 1.0, 0.0, dXs, False, work), 10)
+        result["fused_sgd_backward"] = {"bwd_ms": round(plain_us / 1e3, 4), "bwd_sgd_ms": round(fused_us / 1e3, 4),
+                                        "shape": f"B={B} D={D} C_shard={W.shape[0]}"}
+        del dXs, dWs
+
     # Forward pass of the layer under the paper's two sharding patterns (Section 5.3.2), 8 ways, every
     # device's share run one after another on this GPU: SP1 = 8 class shards (fwd + combine), SP2 = 8
     # contraction slices (partial logits over all classes, then the reduction an AllReduce would do).

@@ -130,6 +130,23 @@ int ws_split_fc_bwd(const void* X, int64_t ldx,
                     float* db_shard,
                     void* workspace, size_t workspace_bytes, void* stream);
 
+/* Backward call with the weight update folded in.  A mini-batch ends with the gradients, scaled by a
+ * learning rate, updating the parameters (Section 2.1); for the split classifier the gradient of a
+ * shard's weights never leaves its device (Section 1), so the update can be applied where the
+ * gradient is produced and dW_shard need not be written at all:
+ *   W_shard[c][d] <- bf16(W_shard[c][d] - lr * dW[c][d])     in place (dW rounded to bf16 first, as
+ *                                                            ws_split_fc_bwd would have stored it)
+ *   b_shard[c]    <- b_shard[c] - lr * db[c]                 in place, if b_shard is not NULL
+ * dX_partial is computed from the weights as they were before the call.  Everything else as in
+ * ws_split_fc_bwd (same workspace size); lr must be finite (WS_ERR_RANGE).  Plain SGD only:
+ * there are no optimizer states and no fp32 master copy of the weights. */
+int ws_split_fc_bwd_sgd(const void* X, int64_t ldx, void* W_shard, int64_t ldw, float* b_shard,
+                        const float* logsumexp, const int32_t* labels,
+                        int32_t B, int32_t D, int32_t C_shard, int32_t class_offset,
+                        float grad_scale, float lr,
+                        float* dX_partial, int64_t lddx, int32_t accumulate_dx,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
 /* Predictions of one shard.  The paper's split listing (Section 3.1.2) ends the split scope with
  * predictions = Softmax(logits); with the combined log-sum-exp of all shards every shard can write
  * its own columns of that matrix without seeing another shard's logits:

@@ -196,3 +196,11 @@ def sp2_reduce(Z_parts, b, y):
     lse = logsumexp_rows(Z)
     y = np.asarray(y, dtype=np.int64)
     return lse, lse - Z[np.arange(Z.shape[0]), y]
+
+
+def sgd_update(W, b, dW, db, lr):
+    """The last phase of a mini-batch (Section 2.1): the gradients, scaled by the learning rate, update
+    the parameters.  Plain SGD: W - lr * dW, b - lr * db."""
+    Wn = _as64(W) - lr * _as64(dW)
+    bn = None if b is None else _as64(b) - lr * _as64(db)
+    return Wn, bn

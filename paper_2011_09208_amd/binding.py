@@ -38,6 +38,9 @@ lib.ws_split_fc_bwd.restype = ctypes.c_int
 lib.ws_split_fc_bwd.argtypes = [_p, _i64, _p, _i64, _p, _p, _p, _i32, _i32, _i32, _i32, _f32,
                                 _p, _i64, _i32, _p, _i64, _p, _p, _sz, _p]
 
+lib.ws_split_fc_bwd_sgd.restype = ctypes.c_int
+lib.ws_split_fc_bwd_sgd.argtypes = [_p, _i64, _p, _i64, _p, _p, _p, _i32, _i32, _i32, _i32, _f32, _f32,
+                                    _p, _i64, _i32, _p, _sz, _p]
 lib.ws_split_fc_predict.restype = ctypes.c_int
 lib.ws_split_fc_predict.argtypes = [_p, _i64, _p, _i64, _p, _p, _i32, _i32, _i32, _p, _i64, _p]
 
@@ -71,7 +74,7 @@ lib.ws_sp2_reduce_stats.restype = ctypes.c_int
 lib.ws_sp2_reduce_stats.argtypes = [ctypes.POINTER(_p), ctypes.POINTER(_i64), _i32, _p, _p, _i32, _i32, _p, _p, _p]
 
 EXPORTS = ["ws_status_string", "ws_version", "ws_fwd_workspace_bytes", "ws_split_fc_fwd",
-           "ws_combine_partials", "ws_bwd_workspace_bytes", "ws_split_fc_bwd", "ws_split_fc_predict",
+           "ws_combine_partials", "ws_bwd_workspace_bytes", "ws_split_fc_bwd", "ws_split_fc_bwd_sgd", "ws_split_fc_predict",
            "ws_profile_enable", "ws_profile_reset", "ws_profile_kernel_count", "ws_profile_kernel_name",
            "ws_profile_read", "ws_balance_widths",
            "ws_bridge_gather", "ws_bridge_reduce_partition", "ws_bridge_fusable",
@@ -145,6 +148,17 @@ def split_fc_bwd(X, W_shard, b_shard, logsumexp, labels, class_offset, grad_scal
                                _ptr(dX_partial), dX_partial.stride(0), int(bool(accumulate_dx)),
                                _ptr(dW_shard), dW_shard.stride(0), _ptr(db_shard), _ptr(workspace),
                                workspace.numel() * workspace.element_size(), _stream()))
+
+
+def split_fc_bwd_sgd(X, W_shard, b_shard, logsumexp, labels, class_offset, grad_scale, lr, dX_partial,
+                     accumulate_dx, workspace):
+    """As split_fc_bwd, but W_shard (bf16) and b_shard (fp32 or None) are updated in place by -lr * gradient."""
+    B, D = X.shape
+    C = W_shard.shape[0]
+    _check(lib.ws_split_fc_bwd_sgd(_ptr(X), X.stride(0), _ptr(W_shard), W_shard.stride(0), _ptr(b_shard),
+                                   _ptr(logsumexp), _ptr(labels), B, D, C, int(class_offset), float(grad_scale),
+                                   float(lr), _ptr(dX_partial), dX_partial.stride(0), int(bool(accumulate_dx)),
+                                   _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
 
 
 def split_fc_predict(X, W_shard, b_shard, logsumexp, P):

@@ -491,4 +491,42 @@ __device__ __forceinline__ void lds_tile_store_rows(const char* lds, uint16_t* o
     }
 }
 
+// The LDS tile holds a gradient; out[n][m] <- bf16(out[n][m] - lr * tile[n][m]) for the same rows and
+// columns as lds_tile_store_rows, each 16-byte chunk read, updated in fp32 and written back.
+__device__ __forceinline__ void lds_tile_update_rows(const char* lds, uint16_t* out, int64_t ld, int n_valid,
+                                                     int m_valid, float lr) {
+    const int tid = threadIdx.x;
+#pragma unroll 4
+    for (int i = 0; i < 16; ++i) {
+        const int q = tid + NTHREADS * i;
+        const int n = q >> 5, cq = q & 31;
+        if (n < n_valid && cq * 8 < m_valid) {
+            const int g = out_tile_swizzle(n);
+            u32x4 gr = *reinterpret_cast<const u32x4*>(lds + n * 512 + ((cq ^ (g >> 1)) << 4));
+            if (g & 1) gr = __builtin_shufflevector(gr, gr, 2, 3, 0, 1);
+            uint16_t* o = out + (int64_t)n * ld + cq * 8;
+            if (cq * 8 + 8 <= m_valid) {
+                const u32x4 w = *reinterpret_cast<const u32x4*>(o);
+                u32x4 r;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float w0 = __uint_as_float(w[e] << 16), w1 = __uint_as_float(w[e] & 0xffff0000u);
+                    const float g0 = __uint_as_float(gr[e] << 16), g1 = __uint_as_float(gr[e] & 0xffff0000u);
+                    r[e] = pack_bf16(fmaf(-lr, g0, w0), fmaf(-lr, g1, w1));
+                }
+                *reinterpret_cast<u32x4*>(o) = r;
+            } else {
+                const int left = m_valid - cq * 8;
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (e < left) {
+                        const float wv = __uint_as_float((uint32_t)o[e] << 16);
+                        const float gv = __uint_as_float((uint32_t)(uint16_t)(gr[e >> 1] >> (16 * (e & 1))) << 16);
+                        o[e] = (uint16_t)(pack_bf16(fmaf(-lr, gv, wv), 0.0f) & 0xffffu);
+                    }
+            }
+        }
+    }
+}
+
 }  // namespace ws

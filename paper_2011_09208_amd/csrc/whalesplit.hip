@@ -649,6 +649,7 @@ struct FinishArgs {
     float* dX; int64_t lddx; int accumulate;
     const float* db_part; int n_db_parts; int64_t db_stride; // nullptr: no db wanted
     int C; float* db;
+    int sgd; float lr;                                        // sgd: db is the bias, updated in place
     int first_block, n_blocks;
 };
 
@@ -677,7 +678,7 @@ __device__ __forceinline__ void finish_bwd(const FinishArgs& f, int worker) {
         for (int64_t c = me; c < f.C; c += stride) {
             float s = 0.0f;
             for (int t = 0; t < f.n_db_parts; ++t) s += f.db_part[t * f.db_stride + c];
-            f.db[c] = s;
+            f.db[c] = f.sgd ? fmaf(-f.lr, s, f.db[c]) : s;
         }
     }
 }
@@ -687,7 +688,8 @@ struct DwArgs {
     const uint16_t* dZ; int64_t ldz;     // [Bpad][Cpad]
     int D, C, Bpad;
     int nDT, nCT, k_steps;
-    uint16_t* dW; int64_t lddw;
+    uint16_t* dW; int64_t lddw;          // sgd: the weights themselves, updated in place
+    int sgd; float lr;
 };
 
 // dW^T tile: M = features d (A = X^T, k contiguous), N = classes (B operand = dz read k-strided, the
@@ -712,8 +714,10 @@ __global__ __launch_bounds__(NTHREADS) void bwd_dw(DwArgs a, FinishArgs fin) {
     acc_to_lds_bf16(acc, lds);
     __syncthreads();
     const int c_left = a.C - ct * TILE_N, d_left = a.D - dt * TILE_M;
-    lds_tile_store_rows(lds, a.dW + (int64_t)ct * TILE_N * a.lddw + dt * TILE_M, a.lddw,
-                        c_left < TILE_N ? c_left : TILE_N, d_left < TILE_M ? d_left : TILE_M);
+    uint16_t* out = a.dW + (int64_t)ct * TILE_N * a.lddw + dt * TILE_M;
+    const int n_valid = c_left < TILE_N ? c_left : TILE_N, m_valid = d_left < TILE_M ? d_left : TILE_M;
+    if (a.sgd) lds_tile_update_rows(lds, out, a.lddw, n_valid, m_valid, a.lr);
+    else lds_tile_store_rows(lds, out, a.lddw, n_valid, m_valid);
 }
 
 // ---- host side -----------------------------------------------------------------------------------
@@ -901,11 +905,14 @@ int ws_combine_partials(const float* row_max, const float* row_sumexp, const flo
     return launch_status();
 }
 
-int ws_split_fc_bwd(const void* X, int64_t ldx, const void* W_shard, int64_t ldw, const float* b_shard,
-                    const float* logsumexp, const int32_t* labels, int32_t B, int32_t D, int32_t C_shard,
-                    int32_t class_offset, float grad_scale, float* dX_partial, int64_t lddx,
-                    int32_t accumulate_dx, void* dW_shard, int64_t lddw, float* db_shard, void* workspace,
-                    size_t workspace_bytes, void* stream) {
+// The backward call.  sgd = 0: dW_shard / db_shard receive the gradients.  sgd = 1: dW_shard is the weight
+// matrix itself (== W_shard) and db_shard the bias itself (== b_shard or NULL); both are updated in place
+// by the last kernel, after every kernel that reads them.
+static int run_bwd(const void* X, int64_t ldx, const void* W_shard, int64_t ldw, const float* b_shard,
+                   const float* logsumexp, const int32_t* labels, int32_t B, int32_t D, int32_t C_shard,
+                   int32_t class_offset, float grad_scale, float* dX_partial, int64_t lddx,
+                   int32_t accumulate_dx, void* dW_shard, int64_t lddw, float* db_shard, void* workspace,
+                   size_t workspace_bytes, void* stream, int sgd, float lr) {
     if (!logsumexp || !dX_partial || !dW_shard) return WS_ERR_NULL;
     int st = check_fc_common(X, ldx, W_shard, ldw, b_shard, labels, B, D, C_shard, class_offset);
     if (st != WS_OK) return st;
@@ -953,15 +960,36 @@ int ws_split_fc_bwd(const void* X, int64_t ldx, const void* W_shard, int64_t ldw
     w.D = D; w.C = C_shard; w.Bpad = (int)p.Bpad;
     w.nDT = p.nDT; w.nCT = p.nCT; w.k_steps = (B + TILE_K - 1) / TILE_K;
     w.dW = static_cast<uint16_t*>(dW_shard); w.lddw = lddw;
+    w.sgd = sgd; w.lr = lr;
     FinishArgs f;
     f.parts = direct ? nullptr : parts; f.splits = p.splits; f.split_stride = (int64_t)B * D;
     f.B = B; f.D = D; f.dX = dX_partial; f.lddx = lddx; f.accumulate = accumulate_dx;
     f.db_part = db_shard ? db_part : nullptr; f.n_db_parts = 4 * p.nBT; f.db_stride = p.Cpad;
     f.C = C_shard; f.db = db_shard;
+    f.sgd = sgd; f.lr = lr;
     f.first_block = xcd_grid(p.nDT * p.nCT);
     f.n_blocks = (f.parts || f.db_part) ? SIDE_BLOCKS : 0;
     WS_LAUNCH(KID_DW, bwd_dw, dim3(f.first_block + f.n_blocks), dim3(NTHREADS), s, w, f);
     return launch_status();
+}
+
+int ws_split_fc_bwd(const void* X, int64_t ldx, const void* W_shard, int64_t ldw, const float* b_shard,
+                    const float* logsumexp, const int32_t* labels, int32_t B, int32_t D, int32_t C_shard,
+                    int32_t class_offset, float grad_scale, float* dX_partial, int64_t lddx,
+                    int32_t accumulate_dx, void* dW_shard, int64_t lddw, float* db_shard, void* workspace,
+                    size_t workspace_bytes, void* stream) {
+    return run_bwd(X, ldx, W_shard, ldw, b_shard, logsumexp, labels, B, D, C_shard, class_offset, grad_scale,
+                   dX_partial, lddx, accumulate_dx, dW_shard, lddw, db_shard, workspace, workspace_bytes, stream, 0,
+                   0.0f);
+}
+
+int ws_split_fc_bwd_sgd(const void* X, int64_t ldx, void* W_shard, int64_t ldw, float* b_shard,
+                        const float* logsumexp, const int32_t* labels, int32_t B, int32_t D, int32_t C_shard,
+                        int32_t class_offset, float grad_scale, float lr, float* dX_partial, int64_t lddx,
+                        int32_t accumulate_dx, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!(lr == lr) || lr - lr != 0.0f) return WS_ERR_RANGE;          // NaN or infinite learning rate
+    return run_bwd(X, ldx, W_shard, ldw, b_shard, logsumexp, labels, B, D, C_shard, class_offset, grad_scale,
+                   dX_partial, lddx, accumulate_dx, W_shard, ldw, b_shard, workspace, workspace_bytes, stream, 1, lr);
 }
 
 int ws_split_fc_predict(const void* X, int64_t ldx, const void* W_shard, int64_t ldw, const float* b_shard,

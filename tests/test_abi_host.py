@@ -138,3 +138,16 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert res.returncode != 0 and "ONE GPU" in (res.stderr + res.stdout)
+
+
+def test_bwd_sgd_argument_validation(ws):
+    E = {ws.status_string(i): i for i in range(7)}
+
+    def sgd(X=A, ldx=64, W=A, ldw=64, b=None, lse=A, y=A, B=4, D=64, C=8, off=0, g=1.0, lr=0.1, dX=A, lddx=64,
+            acc=0, wsp=A, wsb=1 << 24):
+        return ws.lib.ws_split_fc_bwd_sgd(X, ldx, W, ldw, b, lse, y, B, D, C, off, g, lr, dX, lddx, acc, wsp, wsb, None)
+
+    assert sgd(W=None) == E["WS_ERR_NULL"] and sgd(dX=None) == E["WS_ERR_NULL"]
+    assert sgd(lr=float("nan")) == E["WS_ERR_RANGE"] and sgd(lr=float("inf")) == E["WS_ERR_RANGE"]
+    assert sgd(D=65) == E["WS_ERR_SHAPE"] and sgd(ldw=72, W=A + 8) == E["WS_ERR_ALIGN"]
+    assert sgd(wsb=16) == E["WS_ERR_WORKSPACE"]

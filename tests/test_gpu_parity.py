@@ -384,3 +384,60 @@ def test_predictions_full_size_uneven_shards(H):
     p = inputs.make_config("cfg4")
     H.say(f"[parity] predictions cfg4: B={p.B} D={p.D} C={p.C} shards={p.shards}")
     _predict_parity(H, p, p.shards, tag="predict cfg4")
+
+
+def test_backward_with_fused_sgd_update(H):
+    """ws_split_fc_bwd_sgd against the oracle's update, on two shards with bias: the new weights within
+    bf16 rounding of the result plus the gradient gate times lr, the new bias likewise in fp32, and dX bit
+    for bit what the plain backward call gives (it must use the weights from before the update)."""
+    import torch
+    from oracle import oracle
+    from paper_2011_09208_amd import binding as ws
+    p = inputs.make_inputs("sgd", 300, 256, 1500, w_sigma=0.3, bias_sigma=0.5, seed=61)
+    H.say(f"[parity] fused SGD: B={p.B} D={p.D} C={p.C}, two shards")
+    shards = [(0, 700), (700, 800)]
+    lr, g = 0.05, 1.0 / p.B
+    dev = torch.device("cuda")
+    X = H.dev_bf16(p.X_bits)
+    y = torch.from_numpy(p.labels).to(dev)
+    B, D = p.B, p.D
+    m, s, t = (torch.empty((2, B), device=dev) for _ in range(3))
+    lse, loss = torch.empty(B, device=dev), torch.empty(B, device=dev)
+    work = torch.empty(max(max(ws.fwd_workspace_bytes(B, D, c), ws.bwd_workspace_bytes(B, D, c)) for _, c in shards),
+                       dtype=torch.uint8, device=dev)
+    PW = D + 8                                     # padded pitch: the padding must stay untouched
+    Wp = torch.full((p.C, PW), 5.0, device=dev, dtype=torch.bfloat16)
+    Wp[:, :D] = H.dev_bf16(p.W_bits)
+    W = Wp[:, :D]
+    bias = torch.from_numpy(p.bias).to(dev)
+    for i, (off, c) in enumerate(shards):
+        ws.split_fc_fwd(X, W[off:off + c], bias[off:off + c], y, off, m[i], s[i], t[i], work)
+    ws.combine_partials(m, s, t, lse, loss, None)
+    # plain backward first (keeps W), then the fused one
+    dX_ref = torch.empty((B, D), device=dev)
+    dW = torch.empty((p.C, D), device=dev, dtype=torch.bfloat16)
+    db = torch.empty(p.C, device=dev)
+    for i, (off, c) in enumerate(shards):
+        ws.split_fc_bwd(X, W[off:off + c], bias[off:off + c], lse, y, off, g, dX_ref, i > 0, dW[off:off + c],
+                        db[off:off + c], work)
+    dX = torch.full((B, D), float("nan"), device=dev)
+    for i, (off, c) in enumerate(shards):
+        ws.split_fc_bwd_sgd(X, W[off:off + c], bias[off:off + c], lse, y, off, g, lr, dX, i > 0, work)
+    torch.cuda.synchronize()
+    assert torch.equal(dX.view(torch.int32), dX_ref.view(torch.int32))
+    W64, X64 = inputs.bf16_bits_to_f64(p.W_bits), inputs.bf16_bits_to_f64(p.X_bits)
+    ref = oracle.unsharded(X64, W64, p.bias.astype(np.float64), p.labels.astype(np.int64), g)
+    Wn, bn = oracle.sgd_update(W64, p.bias.astype(np.float64), ref["dW"], ref["db"], lr)
+    got_W = H.bf16_to_f64(Wp)
+    assert np.all(got_W[:, D:] == 5.0)
+    tol_W = 2.0 ** -8 * np.abs(Wn) + lr * H.GRAD_REL_TO_MAX * np.max(np.abs(ref["dW"]))
+    assert np.all(np.abs(got_W[:, :D] - Wn) <= tol_W), float(np.max(np.abs(got_W[:, :D] - Wn)))
+    assert np.abs(got_W[:, :D] - W64).max() > 0                      # the update did something
+    got_b = bias.cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got_b - bn) <= 1e-6 * np.abs(bn) + lr * H.GRAD_REL_TO_MAX * np.max(np.abs(ref["db"])))
+    # the fused call equals "plain backward, then W - lr * (its bf16 dW), rounded to bf16" up to the last
+    # bit of a few entries (the kernel uses one fused multiply-add, numpy a multiply and an add)
+    two_step = inputs.f32_to_bf16_bits(inputs.bf16_bits_to_f32(p.W_bits)
+                                       + np.float32(-lr) * H.bf16_to_f64(dW).astype(np.float32))
+    agree = (got_W[:, :D] == inputs.bf16_bits_to_f64(two_step)).mean()
+    assert agree > 0.999, agree

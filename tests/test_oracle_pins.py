@@ -322,3 +322,25 @@ def test_sp2_partials_sum_to_the_logits_and_give_the_same_loss():
         assert np.allclose(sum(parts), oracle.logits(X, W, None), rtol=1e-12, atol=1e-13)
         lse, loss = oracle.sp2_reduce(parts, b, y)
         assert np.allclose(lse, ref["lse"], rtol=1e-13) and np.allclose(loss, ref["loss"], rtol=1e-11, atol=1e-13)
+
+
+# ---- the weight update that ends a mini-batch (Section 2.1) ----------------------------------------
+
+def test_sgd_update_descends_by_the_squared_gradient_norm():
+    """First-order Taylor: loss(theta - lr * grad) = loss(theta) - lr * |grad|^2 + O(lr^2).  A wrong sign, a
+    missing factor or swapped gradients fail this."""
+    rng = np.random.default_rng(15)
+    B, D, C = 6, 5, 7
+    X = rng.normal(size=(B, D)); W = rng.normal(size=(C, D)); b = rng.normal(size=C)
+    y = rng.integers(0, C, size=B)
+    ref = oracle.unsharded(X, W, b, y, 1.0)
+    g2 = float((ref["dW"] ** 2).sum() + (ref["db"] ** 2).sum())
+    for lr in (1e-4, 1e-5):
+        Wn, bn = oracle.sgd_update(W, b, ref["dW"], ref["db"], lr)
+        after = oracle.unsharded(X, Wn, bn, y, 1.0)["loss"].sum()
+        drop = ref["loss"].sum() - after
+        assert abs(drop - lr * g2) <= 50 * lr * lr * g2 + 1e-13
+    Wn, bn = oracle.sgd_update(W, b, ref["dW"], ref["db"], 0.0)
+    assert np.array_equal(Wn, W) and np.array_equal(bn, b)
+    Wn, bn = oracle.sgd_update(W, None, ref["dW"], None, 0.5)
+    assert bn is None and np.allclose(Wn, W - 0.5 * ref["dW"], rtol=0, atol=0)
