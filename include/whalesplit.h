@@ -160,6 +160,21 @@ int ws_split_fc_predict(const void* X, int64_t ldx, const void* W_shard, int64_t
                         int32_t B, int32_t D, int32_t C_shard,
                         void* P, int64_t ldp, void* stream);
 
+/* Arg-max predictions.  The class a row is assigned to is the arg-max of Softmax(logits), which is the
+ * arg-max of the logits: every shard reports its best class and that class's logit, and the shards'
+ * candidates merge by the larger logit (the partial arg-max merge that stands in for gathering the
+ * split-dimension outputs, Section 3.2.3).  Among equal logits the lowest class id wins, in both calls.
+ *   ws_split_fc_top1   top_logit[i] = max_c z[i][c],  top_class[i] = class_offset + argmax_c z[i][c]
+ *                      (fp32 / int32 [B]); workspace of ws_fwd_workspace_bytes
+ *   ws_combine_top1    top_logit / top_class [S][shard_stride] -> best_logit / best_class [B]
+ * The comparison is made on the fp32 logits the kernel computes. */
+int ws_split_fc_top1(const void* X, int64_t ldx, const void* W_shard, int64_t ldw, const float* b_shard,
+                     int32_t B, int32_t D, int32_t C_shard, int32_t class_offset,
+                     float* top_logit, int32_t* top_class,
+                     void* workspace, size_t workspace_bytes, void* stream);
+int ws_combine_top1(const float* top_logit, const int32_t* top_class, int32_t S, int32_t B,
+                    int64_t shard_stride, float* best_logit, int32_t* best_class, void* stream);
+
 /* Hardware-aware shard widths (HOST pointers only; no GPU work).  Section 3.3.1: a `split`
  * TaskGraph is balanced over devices of unequal capacity by uneven sharding in the splitting
  * dimension; load ratios proportional to the devices' FLOP/s minimise the formula given there,

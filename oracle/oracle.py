@@ -204,3 +204,18 @@ def sgd_update(W, b, dW, db, lr):
     Wn = _as64(W) - lr * _as64(dW)
     bn = None if b is None else _as64(b) - lr * _as64(db)
     return Wn, bn
+
+
+def top1(X, W_s, b_s, class_offset):
+    """The shard's arg-max prediction: (max_c Z_ic, class_offset + argmax_c Z_ic), first maximum on ties."""
+    Z = logits(X, W_s, b_s)
+    idx = Z.argmax(axis=1)
+    return Z[np.arange(Z.shape[0]), idx], idx + class_offset
+
+
+def combine_top1(vals, classes):
+    """Merge of the shards' candidates: larger logit, lower class id among equals."""
+    vals, classes = np.stack(vals), np.stack(classes)
+    best_v = vals.max(axis=0)
+    masked = np.where(vals == best_v[None, :], classes, np.iinfo(np.int64).max)
+    return best_v, masked.min(axis=0)

@@ -41,6 +41,10 @@ lib.ws_split_fc_bwd.argtypes = [_p, _i64, _p, _i64, _p, _p, _p, _i32, _i32, _i32
 lib.ws_split_fc_bwd_sgd.restype = ctypes.c_int
 lib.ws_split_fc_bwd_sgd.argtypes = [_p, _i64, _p, _i64, _p, _p, _p, _i32, _i32, _i32, _i32, _f32, _f32,
                                     _p, _i64, _i32, _p, _sz, _p]
+lib.ws_split_fc_top1.restype = ctypes.c_int
+lib.ws_split_fc_top1.argtypes = [_p, _i64, _p, _i64, _p, _i32, _i32, _i32, _i32, _p, _p, _p, _sz, _p]
+lib.ws_combine_top1.restype = ctypes.c_int
+lib.ws_combine_top1.argtypes = [_p, _p, _i32, _i32, _i64, _p, _p, _p]
 lib.ws_split_fc_predict.restype = ctypes.c_int
 lib.ws_split_fc_predict.argtypes = [_p, _i64, _p, _i64, _p, _p, _i32, _i32, _i32, _p, _i64, _p]
 
@@ -74,7 +78,7 @@ lib.ws_sp2_reduce_stats.restype = ctypes.c_int
 lib.ws_sp2_reduce_stats.argtypes = [ctypes.POINTER(_p), ctypes.POINTER(_i64), _i32, _p, _p, _i32, _i32, _p, _p, _p]
 
 EXPORTS = ["ws_status_string", "ws_version", "ws_fwd_workspace_bytes", "ws_split_fc_fwd",
-           "ws_combine_partials", "ws_bwd_workspace_bytes", "ws_split_fc_bwd", "ws_split_fc_bwd_sgd", "ws_split_fc_predict",
+           "ws_combine_partials", "ws_bwd_workspace_bytes", "ws_split_fc_bwd", "ws_split_fc_bwd_sgd", "ws_split_fc_predict", "ws_split_fc_top1", "ws_combine_top1",
            "ws_profile_enable", "ws_profile_reset", "ws_profile_kernel_count", "ws_profile_kernel_name",
            "ws_profile_read", "ws_balance_widths",
            "ws_bridge_gather", "ws_bridge_reduce_partition", "ws_bridge_fusable",
@@ -159,6 +163,24 @@ def split_fc_bwd_sgd(X, W_shard, b_shard, logsumexp, labels, class_offset, grad_
                                    _ptr(logsumexp), _ptr(labels), B, D, C, int(class_offset), float(grad_scale),
                                    float(lr), _ptr(dX_partial), dX_partial.stride(0), int(bool(accumulate_dx)),
                                    _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+
+def split_fc_top1(X, W_shard, b_shard, class_offset, top_logit, top_class, workspace):
+    """top_logit fp32 [B], top_class int32 [B] <- the shard's best class per row."""
+    B, D = X.shape
+    C = W_shard.shape[0]
+    _check(lib.ws_split_fc_top1(_ptr(X), X.stride(0), _ptr(W_shard), W_shard.stride(0), _ptr(b_shard), B, D, C,
+                                int(class_offset), _ptr(top_logit), _ptr(top_class), _ptr(workspace),
+                                workspace.numel() * workspace.element_size(), _stream()))
+
+
+def combine_top1(top_logit, top_class, best_logit, best_class):
+    """[S, B] candidates -> [B] winners."""
+    S, B = top_logit.shape
+    stride = top_logit.stride(0) if S > 1 else max(B, top_logit.stride(0))
+    assert top_class.shape == top_logit.shape and (S == 1 or top_class.stride(0) == stride)
+    _check(lib.ws_combine_top1(_ptr(top_logit), _ptr(top_class), S, B, stride, _ptr(best_logit), _ptr(best_class),
+                               _stream()))
 
 
 def split_fc_predict(X, W_shard, b_shard, logsumexp, P):

@@ -9,6 +9,7 @@
 //                      [row][class]; column sums of the tile (db partials); its surplus workgroups
 //                      write X^T for the dW contraction
 //   predict_probs      softmax probabilities of the shard's classes, exp(z - lse), bf16
+//   top1_logits        the shard's arg-max class and its logit per row (+ merge_top1, also used across shards)
 //   bwd_dx             dX_partial = dz . W_s, split along the class contraction; partial sums
 //   bwd_dw             dW_s = dz^T . X; its surplus workgroups sum the split-K partials of dX
 //                      (optionally accumulating into the caller's dX) and the db partials
@@ -593,6 +594,75 @@ __global__ __launch_bounds__(NTHREADS) void predict_probs(FcArgs a, const float*
                         c_left < TILE_M ? c_left : TILE_M);
 }
 
+// ---- arg-max predictions --------------------------------------------------------------------------
+// The better of two (logit, class) candidates: the larger logit, the lower class id among equals.
+__device__ __forceinline__ void better_of(float& v, int& c, float v2, int c2) {
+    if (v2 > v || (v2 == v && c2 < c)) {
+        v = v2;
+        c = c2;
+    }
+}
+
+// Top-1 of every row over one 256-class tile: the logits GEMM of fwd_logits_stats with an arg-max
+// epilogue.  Partial (logit, shard-local class) pairs go to part_val / part_cls [class tile][row].
+__global__ __launch_bounds__(NTHREADS) void top1_logits(FcArgs a, float* __restrict__ part_val,
+                                                         int* __restrict__ part_cls) {
+    __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
+    float* sbias = reinterpret_cast<float*>(lds);
+    float* red_v = sbias + 256;                              // [2][256]
+    int* red_c = reinterpret_cast<int*>(red_v + 512);
+    const int tile = xcd_logical_tile(a.nBT * a.nCT);
+    if (tile < 0) return;
+    const int ct = tile / a.nBT, bt = tile % a.nBT;
+    acc_t acc;
+    logits_tile(acc, a, ct, bt, lds, sbias);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 2, wn = wave & 3, g = lane >> 4, jl = lane & 15;
+    const int cw0 = ct * TILE_M + wm * WAVE_M;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        float best = NEG_INF;
+        int cls = INT_MAX;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                if (acc[mt][nt][v] > best) {                 // classes are visited in increasing order
+                    best = acc[mt][nt][v];
+                    cls = cw0 + acc_row(mt, v, g);
+                }
+        better_of(best, cls, lane_xor(best, 16), __shfl_xor(cls, 16, 64));
+        better_of(best, cls, lane_xor(best, 32), __shfl_xor(cls, 32, 64));
+        if (g == 0) {
+            red_v[wm * 256 + wn * WAVE_N + 16 * nt + jl] = best;
+            red_c[wm * 256 + wn * WAVE_N + 16 * nt + jl] = cls;
+        }
+    }
+    __syncthreads();
+    if (tid < 256) {
+        float v = red_v[tid];
+        int c = red_c[tid];
+        better_of(v, c, red_v[256 + tid], red_c[256 + tid]);
+        const int64_t o = (int64_t)ct * a.Bpad + bt * TILE_N + tid;
+        part_val[o] = v;
+        part_cls[o] = c;
+    }
+}
+
+// Merges candidates of one row: n candidates `stride` apart; `base` is added to the winning class.
+// One thread per row (the candidate lists are a few hundred entries of a few MB in total).
+__global__ __launch_bounds__(256) void merge_top1(const float* __restrict__ val, const int* __restrict__ cls, int n,
+                                                  int64_t stride, int B, int base, float* __restrict__ out_val,
+                                                  int* __restrict__ out_cls) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= B) return;
+    float v = NEG_INF;
+    int c = INT_MAX;
+    for (int t = 0; t < n; ++t) better_of(v, c, val[t * stride + i], cls[t * stride + i]);
+    out_val[i] = v;
+    out_cls[i] = c == INT_MAX ? c : c + base;
+}
+
 struct DxArgs {
     const uint16_t* dZ; int64_t ldz;     // [Bpad][Cpad]
     const uint16_t* W; int64_t ldw;      // [C][D]
@@ -793,10 +863,10 @@ static int check_fc_common(const void* X, int64_t ldx, const void* W, int64_t ld
 // When enabled, every kernel launch is bracketed by a pair of events recorded on the launch stream.
 // The pairs come from a pool created by ws_profile_enable; when the pool is used up, launches go
 // untimed.  Not thread safe; meant for benchmarks.
-enum KernelId { KID_FWD = 0, KID_MERGE, KID_COMBINE, KID_MEAN, KID_DZ, KID_DX, KID_DW, KID_PREDICT, KID_COUNT };
+enum KernelId { KID_FWD = 0, KID_MERGE, KID_COMBINE, KID_MEAN, KID_DZ, KID_DX, KID_DW, KID_PREDICT, KID_TOP1, KID_TOP1_MERGE, KID_COUNT };
 static const char* const kKernelNames[KID_COUNT] = {"fwd_logits_stats", "merge_class_tiles", "combine_partials",
                                                     "mean_loss", "bwd_recompute_dz", "bwd_dx", "bwd_dw",
-                                                    "predict_probs"};
+                                                    "predict_probs", "top1_logits", "merge_top1"};
 struct ProfState {
     bool on = false;
     int capacity = 0, used = 0;
@@ -1013,6 +1083,49 @@ int ws_split_fc_predict(const void* X, int64_t ldx, const void* W_shard, int64_t
     hipStream_t s = static_cast<hipStream_t>(stream);
     WS_LAUNCH(KID_PREDICT, predict_probs, dim3(xcd_grid(a.nBT * a.nCT)), dim3(NTHREADS), s, a, logsumexp,
               static_cast<uint16_t*>(P), ldp);
+    return launch_status();
+}
+
+int ws_split_fc_top1(const void* X, int64_t ldx, const void* W_shard, int64_t ldw, const float* b_shard, int32_t B,
+                     int32_t D, int32_t C_shard, int32_t class_offset, float* top_logit, int32_t* top_class,
+                     void* workspace, size_t workspace_bytes, void* stream) {
+    if (!X || !W_shard || !top_logit || !top_class) return WS_ERR_NULL;
+    if (!shape_ok(B, D, C_shard)) return WS_ERR_SHAPE;
+    if (ldx < D || ldw < D) return WS_ERR_SHAPE;
+    if (!fits_32bit_offsets(B, ldx) || !fits_32bit_offsets(C_shard, ldw)) return WS_ERR_SHAPE;
+    if (class_offset < 0 || (int64_t)class_offset + C_shard > INT32_MAX) return WS_ERR_RANGE;
+    if (!aligned(X, 16) || !aligned(W_shard, 16) || ldx % 8 || ldw % 8) return WS_ERR_ALIGN;
+    if (!aligned(top_logit, 4) || !aligned(top_class, 4) || (b_shard && !aligned(b_shard, 4))) return WS_ERR_ALIGN;
+    if (!workspace || workspace_bytes < fwd_bytes(B, C_shard)) return WS_ERR_WORKSPACE;
+    if (!aligned(workspace, 16)) return WS_ERR_ALIGN;
+    FcArgs a;
+    a.X = static_cast<const uint16_t*>(X); a.ldx = ldx;
+    a.W = static_cast<const uint16_t*>(W_shard); a.ldw = ldw;
+    a.bias = b_shard; a.labels = nullptr;
+    a.B = B; a.D = D; a.C = C_shard; a.class_offset = class_offset;
+    a.Bpad = (int)round_up(B, 256);
+    a.nBT = a.Bpad / 256;
+    a.nCT = (int)(round_up(C_shard, 256) / 256);
+    a.plan = plan_tiles(a.nBT * a.nCT, false);
+    float* part_val = static_cast<float*>(workspace);
+    int* part_cls = reinterpret_cast<int*>(part_val + (size_t)a.nCT * a.Bpad);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    WS_LAUNCH(KID_TOP1, top1_logits, dim3(xcd_grid(a.nBT * a.nCT)), dim3(NTHREADS), s, a, part_val, part_cls);
+    WS_LAUNCH(KID_TOP1_MERGE, merge_top1, dim3((B + 255) / 256), dim3(256), s, part_val, part_cls, a.nCT,
+              (int64_t)a.Bpad, B, class_offset, top_logit, top_class);
+    return launch_status();
+}
+
+int ws_combine_top1(const float* top_logit, const int32_t* top_class, int32_t S, int32_t B, int64_t shard_stride,
+                    float* best_logit, int32_t* best_class, void* stream) {
+    if (!top_logit || !top_class || !best_logit || !best_class) return WS_ERR_NULL;
+    if (B <= 0 || shard_stride < B) return WS_ERR_SHAPE;
+    if (S < 1 || S > 65536) return WS_ERR_RANGE;
+    if (!aligned(top_logit, 4) || !aligned(top_class, 4) || !aligned(best_logit, 4) || !aligned(best_class, 4))
+        return WS_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    WS_LAUNCH(KID_TOP1_MERGE, merge_top1, dim3((B + 255) / 256), dim3(256), s, top_logit, top_class, S, shard_stride,
+              B, 0, best_logit, best_class);
     return launch_status();
 }
 

@@ -151,3 +151,17 @@ def test_bwd_sgd_argument_validation(ws):
     assert sgd(lr=float("nan")) == E["WS_ERR_RANGE"] and sgd(lr=float("inf")) == E["WS_ERR_RANGE"]
     assert sgd(D=65) == E["WS_ERR_SHAPE"] and sgd(ldw=72, W=A + 8) == E["WS_ERR_ALIGN"]
     assert sgd(wsb=16) == E["WS_ERR_WORKSPACE"]
+
+
+def test_top1_argument_validation(ws):
+    E = {ws.status_string(i): i for i in range(7)}
+
+    def top(X=A, ldx=64, W=A, ldw=64, b=None, B=4, D=64, C=8, off=0, v=A, c=A, wsp=A, wsb=1 << 20):
+        return ws.lib.ws_split_fc_top1(X, ldx, W, ldw, b, B, D, C, off, v, c, wsp, wsb, None)
+
+    assert top(v=None) == E["WS_ERR_NULL"] and top(c=None) == E["WS_ERR_NULL"]
+    assert top(D=96) == E["WS_ERR_SHAPE"] and top(off=-1) == E["WS_ERR_RANGE"]
+    assert top(c=A + 2) == E["WS_ERR_ALIGN"] and top(wsb=8) == E["WS_ERR_WORKSPACE"]
+    assert ws.lib.ws_combine_top1(A, A, 0, 4, 4, A, A, None) == E["WS_ERR_RANGE"]
+    assert ws.lib.ws_combine_top1(A, A, 2, 4, 3, A, A, None) == E["WS_ERR_SHAPE"]
+    assert ws.lib.ws_combine_top1(A, None, 2, 4, 4, A, A, None) == E["WS_ERR_NULL"]

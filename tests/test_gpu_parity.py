@@ -441,3 +441,82 @@ def test_backward_with_fused_sgd_update(H):
                                        + np.float32(-lr) * H.bf16_to_f64(dW).astype(np.float32))
     agree = (got_W[:, :D] == inputs.bf16_bits_to_f64(two_step)).mean()
     assert agree > 0.999, agree
+
+
+def _top1_run(H, X_bits, W_bits, bias, shards):
+    import torch
+    from paper_2011_09208_amd import binding as ws
+    X, W = H.dev_bf16(X_bits), H.dev_bf16(W_bits)
+    B, D = X.shape
+    b = None if bias is None else torch.from_numpy(np.ascontiguousarray(bias, dtype=np.float32)).cuda()
+    S = len(shards)
+    tv = torch.full((S, B), float("nan"), device="cuda")
+    tc = torch.full((S, B), -7, device="cuda", dtype=torch.int32)
+    work = torch.empty(max(ws.fwd_workspace_bytes(B, D, c) for _, c in shards), dtype=torch.uint8, device="cuda")
+    work.fill_(0xFF)
+    for i, (off, c) in enumerate(shards):
+        ws.split_fc_top1(X, W[off:off + c], None if b is None else b[off:off + c], off, tv[i], tc[i], work)
+    bv = torch.full((B,), float("nan"), device="cuda")
+    bc = torch.full((B,), -7, device="cuda", dtype=torch.int32)
+    ws.combine_top1(tv, tc, bv, bc)
+    torch.cuda.synchronize()
+    return tv.cpu().numpy(), tc.cpu().numpy(), bv.cpu().numpy(), bc.cpu().numpy()
+
+
+def test_top1_exact_cases(H):
+    """Integer-valued logits are exact in fp32, so the arg-max and the tie rule can be checked bit for bit:
+    W = 0 and b_c = c gives the last class of every shard; a constant bias ties all classes and the lowest id
+    must win, inside a shard and across shards."""
+    B, D, C = 70, 64, 1000
+    shards = [(0, 300), (300, 1), (301, 699)]
+    Xb = inputs.make_inputs("top1", B, D, C, seed=71).X_bits
+    Wz = np.zeros((C, D), dtype=np.uint16)
+    H.say("[parity] top-1: exact integer logits and ties")
+    tv, tc, bv, bc = _top1_run(H, Xb, Wz, np.arange(C, dtype=np.float32), shards)
+    for i, (off, c) in enumerate(shards):
+        assert np.all(tc[i] == off + c - 1) and np.all(tv[i] == float(off + c - 1))
+    assert np.all(bc == C - 1) and np.all(bv == float(C - 1))
+    tv, tc, bv, bc = _top1_run(H, Xb, Wz, np.full(C, 3.0, dtype=np.float32), shards)
+    for i, (off, c) in enumerate(shards):
+        assert np.all(tc[i] == off) and np.all(tv[i] == 3.0)
+    assert np.all(bc == 0)
+    # descending bias: the first class of every shard, and class 0 overall
+    tv, tc, bv, bc = _top1_run(H, Xb, Wz, -np.arange(C, dtype=np.float32), shards)
+    assert np.all(tc == np.array([o for o, _ in shards])[:, None]) and np.all(bc == 0)
+
+
+def _top1_parity(H, p, shards, tag):
+    from oracle import oracle
+    H.say(f"[parity] {tag}: top-1 B={p.B} D={p.D} C={p.C} shards={shards if len(shards) < 6 else len(shards)}")
+    tv, tc, bv, bc = _top1_run(H, p.X_bits, p.W_bits, p.bias, shards)
+    X64, W64 = inputs.bf16_bits_to_f64(p.X_bits), inputs.bf16_bits_to_f64(p.W_bits)
+    b64 = None if p.bias is None else p.bias.astype(np.float64)
+    Z = oracle.logits(X64, W64, b64)
+    tol = H.LSE_ABS * max(1.0, float(np.max(np.abs(Z))))
+    rows = np.arange(p.B)
+    refs = []
+    for i, (off, c) in enumerate(shards):
+        rv, rc = oracle.top1(X64, W64[off:off + c], None if b64 is None else b64[off:off + c], off)
+        refs.append((rv, rc))
+        assert np.all((tc[i] >= off) & (tc[i] < off + c))
+        assert np.max(np.abs(tv[i] - rv)) <= tol                       # the best logit itself
+        assert np.all(Z[rows, tc[i]] >= rv - 2 * tol)                  # the chosen class is a maximum up to rounding
+        part = np.partition(Z[:, off:off + c], -2, axis=1) if c > 1 else None
+        clear = np.ones(p.B, dtype=bool) if c == 1 else (part[:, -1] - part[:, -2] > 2 * tol)
+        assert np.array_equal(tc[i][clear], rc[clear])                 # exact wherever the decision is not a near-tie
+    rbv, rbc = oracle.combine_top1([r[0] for r in refs], [r[1] for r in refs])
+    part = np.partition(Z, -2, axis=1)
+    clear = part[:, -1] - part[:, -2] > 2 * tol
+    assert np.max(np.abs(bv - rbv)) <= tol and np.array_equal(bc[clear], rbc[clear])
+    assert np.all(Z[rows, bc] >= rbv - 2 * tol)
+    # the merge itself is integer work on the candidates it was given: bit-exact against the oracle's merge
+    mv, mc = oracle.combine_top1(list(tv.astype(np.float64)), list(tc.astype(np.int64)))
+    assert np.array_equal(mc, bc) and np.array_equal(mv.astype(np.float32), bv)
+    H.say(f"[parity] {tag}: top-1 clear rows {int(clear.sum())} of {p.B}, all agree")
+
+
+def test_top1_ragged_and_full_size(H):
+    q = inputs.make_inputs("top1", 300, 128, 1031, w_sigma=0.4, bias_sigma=1.0, seed=72)
+    _top1_parity(H, q, [(0, 5), (5, 515), (520, 511)], "ragged")
+    p = inputs.make_config("cfg4")
+    _top1_parity(H, p, p.shards, "cfg4")

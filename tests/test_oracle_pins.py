@@ -344,3 +344,27 @@ def test_sgd_update_descends_by_the_squared_gradient_norm():
     assert np.array_equal(Wn, W) and np.array_equal(bn, b)
     Wn, bn = oracle.sgd_update(W, None, ref["dW"], None, 0.5)
     assert bn is None and np.allclose(Wn, W - 0.5 * ref["dW"], rtol=0, atol=0)
+
+
+# ---- arg-max predictions and their merge across shards ------------------------------------------------
+
+def test_top1_hand_example_ties_and_merge():
+    X = np.array([[1.0], [-1.0]]); W = np.array([[0.0], [2.0], [2.0], [-3.0]])
+    v, c = oracle.top1(X, W, None, 0)
+    assert v.tolist() == [2.0, 3.0] and c.tolist() == [1, 3]        # row 0: classes 1 and 2 tie -> the lower id
+    v0, c0 = oracle.top1(X, W[:2], None, 0)
+    v1, c1 = oracle.top1(X, W[2:], None, 2)
+    assert c0.tolist() == [1, 0] and c1.tolist() == [2, 3]
+    bv, bc = oracle.combine_top1([v0, v1], [c0, c1])
+    assert bv.tolist() == [2.0, 3.0] and bc.tolist() == [1, 3]      # the tie across shards also goes to the lower id
+
+
+def test_top1_merge_equals_argmax_of_the_whole_layer():
+    rng = np.random.default_rng(16)
+    X = rng.normal(size=(40, 6)); W = rng.normal(size=(37, 6)); b = rng.normal(size=37)
+    Z = oracle.logits(X, W, b)
+    parts = [oracle.top1(X, W[o:o + c], b[o:o + c], o) for o, c in [(0, 1), (1, 20), (21, 16)]]
+    bv, bc = oracle.combine_top1([p[0] for p in parts], [p[1] for p in parts])
+    assert np.array_equal(bc, Z.argmax(axis=1)) and np.array_equal(bv, Z.max(axis=1))
+    # the arg-max of the logits is the arg-max of the softmax (monotone), so these are the predictions
+    assert np.array_equal(bc, scipy.special.softmax(Z, axis=1).argmax(axis=1))
