@@ -244,8 +244,9 @@ int ws_bridge_fusable(int32_t gather_dim, int32_t n_src, const int64_t* src_exte
  *   ws_sp2_reduce_stats     z = sum_s Z_partial_s (slice order s = 0 .. S-1) + bias;
  *                           logsumexp[i] = ln sum_c exp(z[i][c]);  loss_rows[i] = logsumexp[i] - z[i][labels[i]]
  * X_slice bf16 [B][ldx] and W_slice bf16 [C][ldw] hold D_slice (a multiple of 64) columns of X and
- * W; alignment and size rules as for ws_split_fc_fwd.  Z_partials is a HOST array of S (at most 64)
- * DEVICE pointers, 16-byte aligned, pitches multiples of 4; bias fp32 [C] 16-byte aligned or NULL. */
+ * W; alignment and size rules as for ws_split_fc_fwd.  Z_partial (both calls): 16-byte aligned, pitch a
+ * multiple of 4 elements and >= C.  Z_partials is a HOST array of S (at most 64) DEVICE pointers;
+ * bias fp32 [C] 16-byte aligned or NULL. */
 int ws_sp2_partial_logits(const void* X_slice, int64_t ldx, const void* W_slice, int64_t ldw,
                           int32_t B, int32_t D_slice, int32_t C,
                           float* Z_partial, int64_t ldz, void* stream);

@@ -52,13 +52,15 @@ def logsumexp_rows(Z):
     return m + np.log(np.exp(Z - m[:, None]).sum(axis=1))
 
 
-def unsharded(X, W, b, y, g=1.0):
+def unsharded(X, W, b, y, g=1.0, want_dW=True):
     """Softmax cross-entropy of the whole layer and all its gradients.
 
     Returns a dict with
       lse [B], loss [B], loss_mean (scalar),
       dZ [B, C] = g * (softmax(Z) - onehot(y)),
       dX [B, D] = dZ @ W,  dW [C, D] = dZ.T @ X,  db [C] = column sums of dZ.
+    With want_dW=False the [C, D] product is left out (None): for a very wide layer it is the one
+    output that does not fit a host comfortably.
     """
     X = _as64(X)
     W = _as64(W)
@@ -77,7 +79,7 @@ def unsharded(X, W, b, y, g=1.0):
         "loss_mean": loss.mean() if B else _F(0.0),
         "dZ": dZ,
         "dX": dZ @ W,
-        "dW": dZ.T @ X,
+        "dW": dZ.T @ X if want_dW else None,
         "db": dZ.sum(axis=0),
     }
 
@@ -162,7 +164,7 @@ def unsharded_chunked(X, W, b, y, g=1.0, rows_per_chunk=512, want_dW=True):
     db = np.zeros(C, dtype=_F)
     for r0 in range(0, B, rows_per_chunk):
         r1 = min(B, r0 + rows_per_chunk)
-        part = unsharded(X[r0:r1], W, b, y[r0:r1], g)
+        part = unsharded(X[r0:r1], W, b, y[r0:r1], g, want_dW=want_dW)
         lse[r0:r1] = part["lse"]
         loss[r0:r1] = part["loss"]
         dX[r0:r1] = part["dX"]

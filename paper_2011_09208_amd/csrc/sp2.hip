@@ -132,9 +132,11 @@ int ws_sp2_partial_logits(const void* X_slice, int64_t ldx, const void* W_slice,
     if (!X_slice || !W_slice || !Z_partial) return WS_ERR_NULL;
     if (B <= 0 || C <= 0 || D_slice <= 0 || D_slice % 64 != 0) return WS_ERR_SHAPE;
     if (ldx < D_slice || ldw < D_slice || ldz < C) return WS_ERR_SHAPE;
+    // Z_partial: what ws_sp2_reduce_stats requires of its inputs, so a buffer accepted here is accepted there
+    if (!al(Z_partial, 16) || ldz % 4) return WS_ERR_ALIGN;
     if (((int64_t)B + 256) * ldx * 2 >= ((int64_t)1 << 32) || ((int64_t)C + 256) * ldw * 2 >= ((int64_t)1 << 32))
         return WS_ERR_SHAPE;
-    if (!al(X_slice, 16) || !al(W_slice, 16) || ldx % 8 || ldw % 8 || !al(Z_partial, 4)) return WS_ERR_ALIGN;
+    if (!al(X_slice, 16) || !al(W_slice, 16) || ldx % 8 || ldw % 8) return WS_ERR_ALIGN;
     Sp2Args a;
     a.X = static_cast<const uint16_t*>(X_slice); a.ldx = ldx;
     a.W = static_cast<const uint16_t*>(W_slice); a.ldw = ldw;

@@ -1129,22 +1129,31 @@ int ws_combine_top1(const float* top_logit, const int32_t* top_class, int32_t S,
     return launch_status();
 }
 
-int ws_profile_enable(int32_t max_launches) {
-    if (g_prof.start) {
-        for (int i = 0; i < g_prof.capacity; ++i) {
-            (void)hipEventDestroy(g_prof.start[i]);
-            (void)hipEventDestroy(g_prof.stop[i]);
-        }
-        delete[] g_prof.start; delete[] g_prof.stop; delete[] g_prof.kid;
-        g_prof = ProfState();
+static void profile_free_pool() {
+    for (int i = 0; i < g_prof.capacity; ++i) {
+        (void)hipEventDestroy(g_prof.start[i]);
+        (void)hipEventDestroy(g_prof.stop[i]);
     }
+    delete[] g_prof.start; delete[] g_prof.stop; delete[] g_prof.kid;
+    g_prof = ProfState();
+}
+
+int ws_profile_enable(int32_t max_launches) {
+    if (g_prof.start) profile_free_pool();
     if (max_launches <= 0) return WS_OK;
     g_prof.start = new hipEvent_t[max_launches];
     g_prof.stop = new hipEvent_t[max_launches];
     g_prof.kid = new int[max_launches];
     for (int i = 0; i < max_launches; ++i) {
-        if (hipEventCreate(&g_prof.start[i]) != hipSuccess || hipEventCreate(&g_prof.stop[i]) != hipSuccess)
+        if (hipEventCreate(&g_prof.start[i]) != hipSuccess) {
+            profile_free_pool();                      // the pairs created so far; timing stays off
             return WS_ERR_HIP;
+        }
+        if (hipEventCreate(&g_prof.stop[i]) != hipSuccess) {
+            (void)hipEventDestroy(g_prof.start[i]);
+            profile_free_pool();
+            return WS_ERR_HIP;
+        }
         g_prof.capacity = i + 1;
     }
     g_prof.on = true;

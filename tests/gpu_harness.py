@@ -1,6 +1,8 @@
 """Helpers for the GPU parity tests: run one training step of the split head through the
 C-ABI binding, run the fp64 oracle on the same bits, and compare to the stated tolerances.
 Not collected by pytest (no test_ prefix)."""
+import json
+import os
 import sys
 
 import numpy as np
@@ -20,6 +22,16 @@ def say(msg):
     sys.stdout.flush()
 
 
+def record(tag, shape, rep):
+    """Appends the achieved errors of one parity case to the file named by WS_PARITY_LOG (one JSON object
+    per line), so that a run of the suite leaves the margins behind and not only pass/fail."""
+    path = os.environ.get("WS_PARITY_LOG")
+    if not path:
+        return
+    with open(path, "a") as f:
+        f.write(json.dumps({"case": tag, "shape": shape, **{k: float(v) for k, v in rep.items()}}) + "\n")
+
+
 def dev_bf16(bits: np.ndarray) -> torch.Tensor:
     return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
 
@@ -29,14 +41,15 @@ def bf16_to_f64(t: torch.Tensor) -> np.ndarray:
 
 
 def run_step(X_bits, W_bits, bias, labels, shards, g=1.0, w_lo=0, want_db=True, loss_mean=False,
-             lse_override=None):
+             lse_override=None, keep_dW=None):
     """fwd on every shard -> combine -> bwd on every shard (dX accumulated across shards).
 
     W_bits holds classes [w_lo, w_lo + rows); `shards` = [(class_offset, C_shard)].
     Returns numpy arrays: per-shard m, s, t [S, B]; lse, loss [B]; dX [B, D];
     dW list of [C_s, D] (float64 upcast of bf16), db list of [C_s].
     `lse_override` [B] replaces the combined log-sum-exp as the backward call's input (used when only
-    some shards of a wider layer are evaluated).
+    some shards of a wider layer are evaluated).  `keep_dW` = indices of the shards whose dW is copied back
+    (default all; the others give None: dW of a very wide layer is gigabytes on the host).
     """
     from paper_2011_09208_amd import binding as ws
 
@@ -76,7 +89,7 @@ def run_step(X_bits, W_bits, bias, labels, shards, g=1.0, w_lo=0, want_db=True, 
     torch.cuda.synchronize()
     out = dict(m=m.cpu().numpy(), s=s.cpu().numpy(), t=t.cpu().numpy(), lse=lse.cpu().numpy(),
                loss=loss.cpu().numpy(), dX=dX.cpu().numpy(),
-               dW=[bf16_to_f64(w) for w in dWs],
+               dW=[bf16_to_f64(w) if keep_dW is None or i in keep_dW else None for i, w in enumerate(dWs)],
                db=[None if d is None else d.cpu().numpy() for d in dbs])
     if loss_mean:
         out["loss_mean"] = float(mean.cpu().numpy()[0])
@@ -114,8 +127,18 @@ def max_rel_to_max(got, ref):
     return float(np.max(np.abs(got - ref)) / scale)
 
 
-def compare(got, ref, labels, shards, tag=""):
-    """Asserts the parity gate; returns a dict of the error figures."""
+def compare(got, ref, labels, shards, tag="", gate="stated"):
+    """Asserts the parity gate; returns a dict of the error figures.
+
+    gate="stated" (the workload configurations): exactly the stated tolerances, nothing added: loss
+    relative error <= 1e-3 per row, log-sum-exp / row max / label logit absolute error <= 2e-3.
+    gate="fp32_floor" (random ragged shapes, where a row's loss can be ~0 when its label happens to be the
+    arg-max): the same absolute gates; the per-row loss gate gets an absolute floor of 16 * 2^-24 * |z|max,
+    the rounding that lse and the label logit carry as fp32 numbers before they are subtracted.
+    gate="large_logits" (the stress cases with |z| of a few hundred): the absolute gates are multiplied by
+    max(1, |z|max), since the fp32 logits themselves are only known to |z| * 2^-24 * (summation error).
+    Every gradient must be within 2e-2 of its largest magnitude in all three."""
+    assert gate in ("stated", "fp32_floor", "large_logits")
     y = np.asarray(labels, dtype=np.int64)
     rep = {}
     for k in ("m", "s", "t", "lse", "loss", "dX"):
@@ -130,13 +153,14 @@ def compare(got, ref, labels, shards, tag=""):
     rep["lse_abs"] = float(np.max(np.abs(got["lse"] - ref["lse"])))
     rep["loss_rel"] = float(np.max(np.abs(got["loss"] - ref["loss"]) / np.maximum(np.abs(ref["loss"]), 1e-30)))
     rep["loss_abs"] = float(np.max(np.abs(got["loss"] - ref["loss"])))
-    zscale = max(1.0, float(np.max(np.abs(ref["m"]))))
+    zmax = float(np.max(np.abs(ref["m"])))
+    zscale = max(1.0, zmax) if gate == "large_logits" else 1.0
     assert rep["row_max_abs"] <= LSE_ABS * zscale, (tag, rep)
-    assert rep["sumexp_rel"] <= 1e-3 + LSE_ABS * zscale, (tag, rep)
+    assert rep["sumexp_rel"] <= 1e-3 + (LSE_ABS * zscale if gate == "large_logits" else 0.0), (tag, rep)
     assert rep["label_logit_abs"] <= LSE_ABS * zscale, (tag, rep)
     assert rep["lse_abs"] <= LSE_ABS * zscale, (tag, rep)
-    # loss can be ~0 for a dominant label logit: gate it relatively where it is not tiny
-    ok = np.abs(got["loss"] - ref["loss"]) <= LOSS_REL * np.abs(ref["loss"]) + LSE_ABS * zscale * 1e-1
+    floor = {"stated": 0.0, "fp32_floor": 16.0 * 2.0 ** -24 * max(1.0, zmax), "large_logits": LSE_ABS * zscale * 1e-1}[gate]
+    ok = np.abs(got["loss"] - ref["loss"]) <= LOSS_REL * np.abs(ref["loss"]) + floor
     assert np.all(ok), (tag, rep)
     rep["dX"] = max_rel_to_max(got["dX"], ref["dX"])
     assert rep["dX"] <= GRAD_REL_TO_MAX, (tag, rep)
@@ -144,8 +168,9 @@ def compare(got, ref, labels, shards, tag=""):
     wscale = max(np.max(np.abs(w)) for w in ref["dW"]) or 1.0     # a one-class layer has zero gradients
     bscale = max(np.max(np.abs(d)) for d in ref["db"]) or 1.0
     for i in range(len(shards)):
-        assert np.all(np.isfinite(got["dW"][i])), f"{tag}: non-finite dW in shard {i}"
-        rep["dW"] = max(rep["dW"], float(np.max(np.abs(got["dW"][i] - ref["dW"][i])) / wscale))
+        if got["dW"][i] is not None:
+            assert np.all(np.isfinite(got["dW"][i])), f"{tag}: non-finite dW in shard {i}"
+            rep["dW"] = max(rep["dW"], float(np.max(np.abs(got["dW"][i] - ref["dW"][i])) / wscale))
         if got["db"][i] is not None:
             assert np.all(np.isfinite(got["db"][i])), f"{tag}: non-finite db in shard {i}"
             rep["db"] = max(rep["db"], float(np.max(np.abs(got["db"][i] - ref["db"][i])) / bscale))

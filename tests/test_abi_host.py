@@ -120,6 +120,8 @@ def test_sp2_argument_validation(ws):
     assert part(Z=None) == E["WS_ERR_NULL"]
     assert part(Ds=32) == E["WS_ERR_SHAPE"] and part(ldz=7) == E["WS_ERR_SHAPE"] and part(ldx=32) == E["WS_ERR_SHAPE"]
     assert part(X=A + 8) == E["WS_ERR_ALIGN"] and part(ldw=68) == E["WS_ERR_ALIGN"] and part(Z=A + 2) == E["WS_ERR_ALIGN"]
+    # the partial-logit buffer must satisfy what the reduction requires of it later
+    assert part(Z=A + 4) == E["WS_ERR_ALIGN"] and part(ldz=10) == E["WS_ERR_ALIGN"]
 
     def red(parts=(A, A), lds=(8, 8), S=None, bias=None, y=A, B=4, C=8, lse=A, loss=A):
         P = (ctypes.c_void_p * len(parts))(*parts)

@@ -253,6 +253,11 @@ def test_chunked_equals_unchunked():
     c = oracle.unsharded_chunked(X, W, b, y, g=0.3, rows_per_chunk=8)
     for k in ("lse", "loss", "dX", "dW", "db"):
         assert np.allclose(a[k], c[k], rtol=1e-12, atol=1e-13), k
+    # leaving the [C, D] product out changes nothing else
+    n = oracle.unsharded_chunked(X, W, b, y, g=0.3, rows_per_chunk=5, want_dW=False)
+    assert n["dW"] is None and oracle.unsharded(X, W, b, y, g=0.3, want_dW=False)["dW"] is None
+    for k in ("lse", "loss", "dX", "db"):
+        assert np.allclose(a[k], n[k], rtol=1e-12, atol=1e-13), k
 
 
 def test_paper_sizes_fixture():
