@@ -56,7 +56,8 @@ typedef enum {
     WS_ERR_ALIGN = 3,      /* pointer or pitch not aligned as required */
     WS_ERR_RANGE = 4,      /* class_offset negative or class range overflows int32; S out of range */
     WS_ERR_WORKSPACE = 5,  /* workspace NULL or smaller than the query says */
-    WS_ERR_HIP = 6         /* the HIP runtime refused a launch */
+    WS_ERR_HIP = 6,        /* the HIP runtime refused a launch */
+    WS_ERR_LIMIT = 7       /* ws_split_fc_fwd_static: the shape needs more than the built-in scratch */
 } ws_status;
 
 /* Human-readable name of a status code (static storage; never NULL). */
@@ -88,6 +89,28 @@ int ws_split_fc_fwd(const void* X, int64_t ldx,
                     int32_t B, int32_t D, int32_t C_shard, int32_t class_offset,
                     float* row_max, float* row_sumexp, float* label_logit,
                     void* workspace, size_t workspace_bytes, void* stream);
+
+/* The forward call for callers that cannot allocate or pass a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and kernels as
+ * ws_split_fc_fwd (bit-identical outputs), but the per-class-tile partials live in a fixed array built
+ * into the library's device code instead of a caller workspace; the call allocates and frees nothing.
+ *   Limit: ws_fwd_workspace_bytes(B, D, C_shard) <= WS_STATIC_SCRATCH_BYTES, else WS_ERR_LIMIT (checked on
+ *   the host with the other arguments, before any HIP call).  16 MiB covers one shard of every workload
+ *   this library is measured on (headline 3.2 MB; B = 8192 x 50 000 classes 12.8 MB).
+ *   Every GPU the library runs on holds its own 16 MiB copy of the array until the process ends.
+ *   The first call on a device looks the array's device address up (hipGetSymbolAddress); make that
+ *   first call outside a stream capture.
+ *   All calls on one GPU share the array: two calls whose kernels may overlap on that GPU (different
+ *   streams, no ordering between them) race on it.  Calls on one stream, or ordered by events, are safe;
+ *   nothing in the array has to be cleared between calls. */
+#define WS_STATIC_SCRATCH_BYTES (16u << 20)
+int ws_split_fc_fwd_static(const void* X, int64_t ldx,
+                           const void* W_shard, int64_t ldw,
+                           const float* b_shard,
+                           const int32_t* labels,
+                           int32_t B, int32_t D, int32_t C_shard, int32_t class_offset,
+                           float* row_max, float* row_sumexp, float* label_logit,
+                           void* stream);
 
 /* Merge the statistics of S shards evaluated on this GPU (no collectives):
  *   m = max_s row_max[s];  sum = sum_s row_sumexp[s] * exp(row_max[s] - m)

@@ -32,6 +32,8 @@ lib.ws_bwd_workspace_bytes.restype = _sz
 lib.ws_bwd_workspace_bytes.argtypes = [_i32, _i32, _i32]
 lib.ws_split_fc_fwd.restype = ctypes.c_int
 lib.ws_split_fc_fwd.argtypes = [_p, _i64, _p, _i64, _p, _p, _i32, _i32, _i32, _i32, _p, _p, _p, _p, _sz, _p]
+lib.ws_split_fc_fwd_static.restype = ctypes.c_int
+lib.ws_split_fc_fwd_static.argtypes = [_p, _i64, _p, _i64, _p, _p, _i32, _i32, _i32, _i32, _p, _p, _p, _p]
 lib.ws_combine_partials.restype = ctypes.c_int
 lib.ws_combine_partials.argtypes = [_p, _p, _p, _i32, _i32, _i64, _p, _p, _p, _p]
 lib.ws_split_fc_bwd.restype = ctypes.c_int
@@ -77,7 +79,9 @@ lib.ws_sp2_partial_logits.argtypes = [_p, _i64, _p, _i64, _i32, _i32, _i32, _p, 
 lib.ws_sp2_reduce_stats.restype = ctypes.c_int
 lib.ws_sp2_reduce_stats.argtypes = [ctypes.POINTER(_p), ctypes.POINTER(_i64), _i32, _p, _p, _i32, _i32, _p, _p, _p]
 
-EXPORTS = ["ws_status_string", "ws_version", "ws_fwd_workspace_bytes", "ws_split_fc_fwd",
+STATIC_SCRATCH_BYTES = 16 << 20
+
+EXPORTS = ["ws_status_string", "ws_version", "ws_fwd_workspace_bytes", "ws_split_fc_fwd", "ws_split_fc_fwd_static",
            "ws_combine_partials", "ws_bwd_workspace_bytes", "ws_split_fc_bwd", "ws_split_fc_bwd_sgd", "ws_split_fc_predict", "ws_split_fc_top1", "ws_combine_top1",
            "ws_profile_enable", "ws_profile_reset", "ws_profile_kernel_count", "ws_profile_kernel_name",
            "ws_profile_read", "ws_balance_widths",
@@ -129,6 +133,15 @@ def split_fc_fwd(X, W_shard, b_shard, labels, class_offset, row_max, row_sumexp,
                                _ptr(labels), B, D, C, int(class_offset), _ptr(row_max), _ptr(row_sumexp),
                                _ptr(label_logit), _ptr(workspace), workspace.numel() * workspace.element_size(),
                                _stream()))
+
+
+def split_fc_fwd_static(X, W_shard, b_shard, labels, class_offset, row_max, row_sumexp, label_logit):
+    """split_fc_fwd without a workspace: the library's built-in device scratch is used (no allocation)."""
+    B, D = X.shape
+    C = W_shard.shape[0]
+    _check(lib.ws_split_fc_fwd_static(_ptr(X), X.stride(0), _ptr(W_shard), W_shard.stride(0), _ptr(b_shard),
+                                      _ptr(labels), B, D, C, int(class_offset), _ptr(row_max), _ptr(row_sumexp),
+                                      _ptr(label_logit), _stream()))
 
 
 def combine_partials(row_max, row_sumexp, label_logit, logsumexp, loss_rows, loss_mean=None):

@@ -17,6 +17,7 @@
 // four thin 256 x 64 tiles each (logits_thin, fwd_stats_thin, dz_thin; plan_tiles on the host).
 #include <hip/hip_runtime.h>
 #include <algorithm>
+#include <atomic>
 #include <limits.h>
 #include <math.h>
 #include <stdint.h>
@@ -859,6 +860,30 @@ static int check_fc_common(const void* X, int64_t ldx, const void* W, int64_t ld
 }
 
 
+// ---- built-in scratch of the entry point that allocates nothing ---------------------------------------
+// A fixed array in the code object stands in for the forward call's workspace.  Every GPU the library
+// runs on holds its own copy at its own address; in host code the array's name is only a handle, so the
+// device address is looked up once per device and kept.
+static __device__ __align__(256) unsigned char scratch[WS_STATIC_SCRATCH_BYTES];
+constexpr int MAX_DEVICES = 64;
+static std::atomic<void*> g_scratch_ptr[MAX_DEVICES];
+
+// Device address of `scratch` on the current device (looked up at the first call on that device).
+static int static_scratch(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return WS_ERR_HIP;
+    void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p == nullptr) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) {
+            (void)hipGetLastError();
+            return WS_ERR_HIP;
+        }
+        g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return WS_OK;
+}
+
 // ---- optional per-kernel timing --------------------------------------------------------------------
 // When enabled, every kernel launch is bracketed by a pair of events recorded on the launch stream.
 // The pairs come from a pool created by ws_profile_enable; when the pool is used up, launches go
@@ -913,11 +938,12 @@ const char* ws_status_string(int status) {
         case WS_ERR_RANGE: return "WS_ERR_RANGE";
         case WS_ERR_WORKSPACE: return "WS_ERR_WORKSPACE";
         case WS_ERR_HIP: return "WS_ERR_HIP";
+        case WS_ERR_LIMIT: return "WS_ERR_LIMIT";
         default: return "WS_ERR_UNKNOWN";
     }
 }
 
-int ws_version(void) { return 1100; }
+int ws_version(void) { return 1200; }
 
 size_t ws_fwd_workspace_bytes(int32_t B, int32_t D, int32_t C_shard) {
     return shape_ok(B, D, C_shard) ? fwd_bytes(B, C_shard) : 0;
@@ -929,17 +955,21 @@ size_t ws_bwd_workspace_bytes(int32_t B, int32_t D, int32_t C_shard) {
     return p.dz_bytes + p.xt_bytes + p.dbp_bytes + p.parts_bytes;
 }
 
-int ws_split_fc_fwd(const void* X, int64_t ldx, const void* W_shard, int64_t ldw, const float* b_shard,
-                    const int32_t* labels, int32_t B, int32_t D, int32_t C_shard, int32_t class_offset,
-                    float* row_max, float* row_sumexp, float* label_logit, void* workspace,
-                    size_t workspace_bytes, void* stream) {
+// Argument checks of the forward call that do not concern the workspace.
+static int check_fwd(const void* X, int64_t ldx, const void* W_shard, int64_t ldw, const float* b_shard,
+                     const int32_t* labels, int32_t B, int32_t D, int32_t C_shard, int32_t class_offset,
+                     float* row_max, float* row_sumexp, float* label_logit) {
     if (!row_max || !row_sumexp || !label_logit) return WS_ERR_NULL;
     int st = check_fc_common(X, ldx, W_shard, ldw, b_shard, labels, B, D, C_shard, class_offset);
     if (st != WS_OK) return st;
     if (!aligned(row_max, 4) || !aligned(row_sumexp, 4) || !aligned(label_logit, 4)) return WS_ERR_ALIGN;
-    if (!workspace || workspace_bytes < fwd_bytes(B, C_shard)) return WS_ERR_WORKSPACE;
-    if (!aligned(workspace, 16)) return WS_ERR_ALIGN;
+    return WS_OK;
+}
 
+// Launches of the forward call; `workspace` holds fwd_bytes(B, C_shard) bytes, 16-byte aligned.
+static int launch_fwd(const void* X, int64_t ldx, const void* W_shard, int64_t ldw, const float* b_shard,
+                      const int32_t* labels, int32_t B, int32_t D, int32_t C_shard, int32_t class_offset,
+                      float* row_max, float* row_sumexp, float* label_logit, void* workspace, void* stream) {
     FcArgs a;
     a.X = static_cast<const uint16_t*>(X); a.ldx = ldx;
     a.W = static_cast<const uint16_t*>(W_shard); a.ldw = ldw;
@@ -957,6 +987,34 @@ int ws_split_fc_fwd(const void* X, int64_t ldx, const void* W_shard, int64_t ldw
     WS_LAUNCH(KID_MERGE, merge_class_tiles, dim3((B + 15) / 16), dim3(1024), s, part_max, part_sum, a.nCT,
                        a.Bpad, B, row_max, row_sumexp);
     return launch_status();
+}
+
+int ws_split_fc_fwd(const void* X, int64_t ldx, const void* W_shard, int64_t ldw, const float* b_shard,
+                    const int32_t* labels, int32_t B, int32_t D, int32_t C_shard, int32_t class_offset,
+                    float* row_max, float* row_sumexp, float* label_logit, void* workspace,
+                    size_t workspace_bytes, void* stream) {
+    int st = check_fwd(X, ldx, W_shard, ldw, b_shard, labels, B, D, C_shard, class_offset, row_max, row_sumexp,
+                       label_logit);
+    if (st != WS_OK) return st;
+    if (!workspace || workspace_bytes < fwd_bytes(B, C_shard)) return WS_ERR_WORKSPACE;
+    if (!aligned(workspace, 16)) return WS_ERR_ALIGN;
+    return launch_fwd(X, ldx, W_shard, ldw, b_shard, labels, B, D, C_shard, class_offset, row_max, row_sumexp,
+                      label_logit, workspace, stream);
+}
+
+int ws_split_fc_fwd_static(const void* X, int64_t ldx, const void* W_shard, int64_t ldw, const float* b_shard,
+                           const int32_t* labels, int32_t B, int32_t D, int32_t C_shard, int32_t class_offset,
+                           float* row_max, float* row_sumexp, float* label_logit, void* stream) {
+    int st = check_fwd(X, ldx, W_shard, ldw, b_shard, labels, B, D, C_shard, class_offset, row_max, row_sumexp,
+                       label_logit);
+    if (st != WS_OK) return st;
+    if (fwd_bytes(B, C_shard) > (size_t)WS_STATIC_SCRATCH_BYTES) return WS_ERR_LIMIT;
+    void* ws_ptr = nullptr;
+    st = static_scratch(&ws_ptr);
+    if (st != WS_OK) return st;
+    // every partial the merge reads is written by the logits kernel of the same call: nothing to clear
+    return launch_fwd(X, ldx, W_shard, ldw, b_shard, labels, B, D, C_shard, class_offset, row_max, row_sumexp,
+                      label_logit, ws_ptr, stream);
 }
 
 int ws_combine_partials(const float* row_max, const float* row_sumexp, const float* label_logit, int32_t S,

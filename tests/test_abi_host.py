@@ -29,9 +29,9 @@ def test_header_symbols_are_exported(ws):
 
 def test_version_and_status_strings(ws):
     assert ws.version() >= 1000
-    names = [ws.status_string(i) for i in range(7)]
+    names = [ws.status_string(i) for i in range(8)]
     assert names == ["WS_OK", "WS_ERR_NULL", "WS_ERR_SHAPE", "WS_ERR_ALIGN", "WS_ERR_RANGE",
-                     "WS_ERR_WORKSPACE", "WS_ERR_HIP"]
+                     "WS_ERR_WORKSPACE", "WS_ERR_HIP", "WS_ERR_LIMIT"]
     assert ws.status_string(99) == "WS_ERR_UNKNOWN"
 
 
@@ -95,6 +95,26 @@ def test_combine_validation(ws):
     assert f(A, A, A, 70000, 4, 4, A, A, None, None) == 4
     assert f(A + 1, A, A, 1, 4, 4, A, A, None, None) == 3
     assert f(A, A, A, 1, 4, 4, A, A, A + 2, None) == 3
+
+
+def test_static_forward_argument_validation(ws):
+    """The entry point without a workspace validates like the forward call and refuses, on the host, a shape
+    whose class-tile partials exceed the built-in scratch."""
+    E = {ws.status_string(i): i for i in range(8)}
+
+    def fwd(X=A, ldx=64, W=A, ldw=64, b=None, y=A, B=4, D=64, C=8, off=0, m=A, s=A, t=A):
+        return ws.lib.ws_split_fc_fwd_static(X, ldx, W, ldw, b, y, B, D, C, off, m, s, t, None)
+
+    assert fwd(X=None) == E["WS_ERR_NULL"] and fwd(t=None) == E["WS_ERR_NULL"]
+    assert fwd(D=65) == E["WS_ERR_SHAPE"] and fwd(ldw=32) == E["WS_ERR_SHAPE"]
+    assert fwd(W=A + 8) == E["WS_ERR_ALIGN"] and fwd(m=A + 2) == E["WS_ERR_ALIGN"]
+    assert fwd(off=-1) == E["WS_ERR_RANGE"]
+    assert ws.fwd_workspace_bytes(8192, 64, 50_000) <= ws.STATIC_SCRATCH_BYTES
+    assert ws.fwd_workspace_bytes(8192, 64, 600_000) > ws.STATIC_SCRATCH_BYTES
+    assert fwd(B=8192, C=600_000) == E["WS_ERR_LIMIT"]
+    assert fwd(B=1 << 20, C=4096) == E["WS_ERR_LIMIT"]
+    text = open(os.path.join(ROOT, "include", "whalesplit.h")).read()
+    assert re.search(r"#define\s+WS_STATIC_SCRATCH_BYTES\s+\(16u\s*<<\s*20\)", text) and ws.STATIC_SCRATCH_BYTES == 16 << 20
 
 
 def test_predict_argument_validation(ws):
