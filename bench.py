@@ -28,17 +28,21 @@ GEMM_KERNELS = ("fwd_logits_stats", "bwd_recompute_dz", "bwd_dx", "bwd_dw")
 
 
 def read_traffic(workload):
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary, if any."""
+    """HBM bytes per launch of every kernel from the committed rocprofv3 --pmc summary of this workload, and
+    the library version that summary was taken with (counters need a profiler run of their own, so the
+    figure cannot be measured inside this program)."""
     path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
     if not os.path.exists(path):
-        return {}
-    out = {}
+        return {}, None
+    out, version = {}, None
     with open(path) as f:
         for line in f:
             parts = line.split()
             if len(parts) >= 2 and parts[0].startswith("traffic_bytes:"):
                 out[parts[0].split(":", 1)[1]] = float(parts[1])
-    return out
+            if len(parts) >= 2 and parts[0] == "library_version:":
+                version = int(parts[1])
+    return out, version
 
 
 def main():
@@ -50,6 +54,13 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the measurements outside the timed step (bridge ends, SP1 vs SP2 forward)")
+    ap.add_argument("--sustain-seconds", type=float, default=2.0,
+                    help="after the timed steps, keep stepping for about this long and report the step time "
+                         "of that loop as `sustained` (0 = skip)")
+    ap.add_argument("--ceiling", action="store_true",
+                    help="instead of the step, measure what the machine allows the GEMM main loop: an MFMA-only "
+                         "loop and the library's main loop as a plain GEMM, on constant and on random operands, "
+                         "with torch.matmul beside them as context; prints one JSON line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (a kernel of known traffic for scaling "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -65,6 +76,9 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; there is no CPU fallback")
+    if args.ceiling:
+        print(json.dumps(measure_ceiling(ws, torch)), flush=True)
+        return
 
     # cfg5 and million time their first shard only (50 000 of 400 000, 125 000 of 1 000 000 classes);
     # the other rows of W are not kept
@@ -149,7 +163,11 @@ def main():
         if k in kernels:
             kernels[k]["GB/s"] = round(nbytes_k / (kernels[k]["avg_ms"] * 1e-3) / 1e9, 1)
     achieved = kernels[dominant]["tflops"]
-    traffic = read_traffic(args.workload).get(dominant)
+    traffic_table, traffic_version = read_traffic(args.workload)
+    traffic = traffic_table.get(dominant) if traffic_version == ws.version() else None
+    traffic_source = (f"profiles/hbm_traffic_{args.workload}.txt, rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of library "
+                      f"version {traffic_version}" if traffic is not None else
+                      f"none for library version {ws.version()} and this workload (counters need their own profiler run)")
     credited = 6.0 * B * D * c_total
     value = B / (ms_per_step * 1e-3)
     # Algorithmic HBM bytes of one launch of each GEMM kernel (operands read once, outputs written once).
@@ -167,10 +185,12 @@ def main():
     if flops_per_launch / alg_bytes[dominant] < balance:
         gbs = alg_bytes[dominant] / (kernels[dominant]["avg_ms"] * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": traffic}
+                    "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": traffic,
+                    "traffic_source": traffic_source}
     else:
         roofline = {"bound": "mfma", "kernel": dominant, "achieved": achieved, "peak": BF16_DENSE_PEAK_TFLOPS,
-                    "unit": "TFLOP/s", "frac": round(achieved / BF16_DENSE_PEAK_TFLOPS, 4), "traffic": traffic}
+                    "unit": "TFLOP/s", "frac": round(achieved / BF16_DENSE_PEAK_TFLOPS, 4), "traffic": traffic,
+                    "traffic_source": traffic_source}
 
     result = {
         "metric": "split-FC fwd+bwd samples/sec at D=2048,C=100K,B=1024; % bf16 MFMA peak",
@@ -194,6 +214,19 @@ def main():
         "roofline": roofline,
         "kernels": kernels,
     }
+
+    if args.sustain_seconds > 0:
+        # the part is power-limited: a burst of 50 steps (75 ms) runs on a cool chip; this is the rate after seconds at load
+        n = max(args.steps, int(args.sustain_seconds * 1e3 / ms_per_step) + 1)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            step()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        result["sustained"] = {"ms_per_step": round(dt * 1e3 / n, 4), "steps": n, "seconds": round(dt, 2),
+                               "value": round(B * n / dt, 1), "unit": "samples/s",
+                               "pct_bf16_mfma_peak_credited_6BDC": round(100.0 * credited * n / dt / (BF16_DENSE_PEAK_TFLOPS * 1e12), 2)}
 
     if not args.no_extras:
         measure_extras(args, result, ws, torch, dev, X, W, y, B, D, C, work, lse, loss)
@@ -249,6 +282,23 @@ def measure_extras(args, result, ws, torch, dev, X, W, y, B, D, C, work, lse, lo
                                         "shape": f"B={B} D={D} C_shard={W.shape[0]}"}
         del dXs, dWs
 
+    # Context only (never the product path): the vendor GEMM library, through torch.matmul, on the three GEMM
+    # shapes of this step with the same operands (bf16 in, bf16 out).
+    if args.workload == "headline":
+        Zt = torch.empty((B, C), device=dev, dtype=torch.bfloat16)
+        dZt = (torch.randn((B, C), device=dev) * 1e-5).to(torch.bfloat16)
+        dXt = torch.empty((B, D), device=dev, dtype=torch.bfloat16)
+        dWt = torch.empty((C, D), device=dev, dtype=torch.bfloat16)
+        fl = 2.0 * B * D * C
+        ctx = {}
+        for name, fn in (("logits = X . W^T", lambda: torch.matmul(X, W.t(), out=Zt)),
+                         ("dX = dz . W", lambda: torch.matmul(dZt, W, out=dXt)),
+                         ("dW = dz^T . X", lambda: torch.matmul(dZt.t(), X, out=dWt))):
+            us = timed(fn, 10)
+            ctx[name] = {"ms": round(us / 1e3, 4), "tflops": round(fl / us / 1e6, 1)}
+        result["context_torch_matmul_bf16"] = ctx
+        del Zt, dZt, dXt, dWt
+
     # Forward pass of the layer under the paper's two sharding patterns (Section 5.3.2), 8 ways, every
     # device's share run one after another on this GPU: SP1 = 8 class shards (fwd + combine), SP2 = 8
     # contraction slices (partial logits over all classes, then the reduction an AllReduce would do).
@@ -280,6 +330,61 @@ def measure_extras(args, result, ws, torch, dev, X, W, y, B, D, C, work, lse, lo
             "max_abs_lse_diff_sp1_vs_one_shard": float((lse1 - lse).abs().max()),
         }
         del zparts
+
+
+def measure_ceiling(ws, torch):
+    """What the machine allows a bf16 GEMM main loop, each figure sustained over about 0.4 s of back-to-back
+    launches: (1) nothing but MFMAs on register operands, (2) the library's main loop alone as a square GEMM,
+    (3) torch.matmul (the vendor library) on the same operands as context; each on constant operands (all ones)
+    and on random ones (standard normal).  The matrix cores are power-limited and the limit depends on the data."""
+    dev = torch.device("cuda:0")
+    out = {"peak_tflops_nominal": BF16_DENSE_PEAK_TFLOPS, "unit": "TFLOP/s", "measurements": []}
+
+    def sustained(fn, flops_per_call, seconds=0.4):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn()
+        e1.record()
+        e1.synchronize()
+        n = max(3, int(seconds * 1e3 / max(e0.elapsed_time(e1), 1e-3)))
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        e1.synchronize()
+        ms = e0.elapsed_time(e1) / n
+        return round(ms, 4), round(flops_per_call / ms / 1e9, 1), n
+
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(0)
+    wgs, rounds = 256, 4000
+    sink = torch.empty(wgs * 512, device=dev)
+    for kind in ("ones", "random"):
+        frag = (torch.ones(16 * 512 * 8, device=dev) if kind == "ones"
+                else torch.randn(16 * 512 * 8, device=dev, generator=gen)).to(torch.bfloat16)
+        ms, tf, n = sustained(lambda: ws.probe_mfma_loop(frag, rounds, wgs, sink), wgs * 8 * rounds * 128 * 16384.0)
+        out["measurements"].append({"what": "MFMA only, operands in registers (256 workgroups x 8 waves)", "operands": kind,
+                                    "ms_per_launch": ms, "tflops": tf, "launches": n})
+    M = N = 4096
+    K = 8192
+    for kind in ("ones", "random"):
+        mk = (lambda r, c: torch.ones((r, c), device=dev).to(torch.bfloat16)) if kind == "ones" else \
+             (lambda r, c: torch.randn((r, c), device=dev, generator=gen).to(torch.bfloat16))
+        A, Bm = mk(M, K), mk(N, K)
+        Cm = torch.empty((N, M), device=dev, dtype=torch.bfloat16)
+        ms, tf, n = sustained(lambda: ws.probe_gemm(A, Bm, Cm), 2.0 * M * N * K)
+        out["measurements"].append({"what": f"library main loop alone, C = A . B^T, {M} x {N} x {K}", "operands": kind,
+                                    "ms_per_launch": ms, "tflops": tf, "launches": n})
+        ref = torch.matmul(Bm[:64].float(), A[:64].float().t())          # C[n][m]
+        err = float((Cm[:64, :64].float() - ref).abs().max() / ref.abs().max())
+        out["measurements"][-1]["max_rel_err_vs_fp32_matmul_sample"] = err
+        ms, tf, n = sustained(lambda: torch.matmul(A, Bm.t(), out=Cm), 2.0 * M * N * K)
+        out["measurements"].append({"what": f"torch.matmul (vendor library, context), {M} x {N} x {K}", "operands": kind,
+                                    "ms_per_launch": ms, "tflops": tf, "launches": n})
+    return out
 
 
 def cpu_baseline(args, result, inputs, p, B, D, C, lse):

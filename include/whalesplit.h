@@ -277,6 +277,20 @@ int ws_sp2_reduce_stats(const float* const* Z_partials, const int64_t* ldz, int3
                         const float* bias, const int32_t* labels, int32_t B, int32_t C,
                         float* logsumexp, float* loss_rows, void* stream);
 
+/* Diagnostics for benchmarks (not part of the paper's method): what the machine allows the GEMM main loop.
+ * The matrix cores of this part are power-limited and the limit depends on the operand values, so the
+ * caller supplies the data (e.g. all ones against random values) and times the launches itself.
+ *   ws_probe_mfma_loop  `workgroups` workgroups of 8 waves; every wave runs `rounds` x 128
+ *                       v_mfma_f32_16x16x32_bf16 (16384 flops each) on operands held in registers.
+ *                       fragments: DEVICE, 16 x 512 x 16 bytes of bf16 values, 16-byte aligned;
+ *                       sink: DEVICE fp32 [workgroups * 512] (receives a checksum so the loop is kept).
+ *   ws_probe_gemm       C[n][m] = sum_k A[m][k] * B[n][k], bf16 in (A [M][lda], B [N][ldb]), bf16 out
+ *                       (C [N][ldc]), fp32 accumulation: the library's shared main loop and output path
+ *                       alone.  M, N multiples of 256, K of 64; 16-byte aligned, pitches multiples of 8. */
+int ws_probe_mfma_loop(const void* fragments, int32_t rounds, int32_t workgroups, float* sink, void* stream);
+int ws_probe_gemm(const void* A, int64_t lda, const void* B, int64_t ldb, int32_t M, int32_t N, int32_t K,
+                  void* C, int64_t ldc, void* stream);
+
 /* Optional per-kernel timing, for benchmarks (not part of the paper's method; host-side state,
  * not thread safe).  ws_profile_enable(n) creates a pool of n event pairs (n <= 0 switches
  * timing off and frees the pool); while the pool lasts, every kernel the library launches is

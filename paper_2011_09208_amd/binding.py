@@ -50,6 +50,11 @@ lib.ws_combine_top1.argtypes = [_p, _p, _i32, _i32, _i64, _p, _p, _p]
 lib.ws_split_fc_predict.restype = ctypes.c_int
 lib.ws_split_fc_predict.argtypes = [_p, _i64, _p, _i64, _p, _p, _i32, _i32, _i32, _p, _i64, _p]
 
+lib.ws_probe_mfma_loop.restype = ctypes.c_int
+lib.ws_probe_mfma_loop.argtypes = [_p, _i32, _i32, _p, _p]
+lib.ws_probe_gemm.restype = ctypes.c_int
+lib.ws_probe_gemm.argtypes = [_p, _i64, _p, _i64, _i32, _i32, _i32, _p, _i64, _p]
+
 lib.ws_profile_enable.restype = ctypes.c_int
 lib.ws_profile_enable.argtypes = [_i32]
 lib.ws_profile_reset.restype = ctypes.c_int
@@ -86,7 +91,7 @@ EXPORTS = ["ws_status_string", "ws_version", "ws_fwd_workspace_bytes", "ws_split
            "ws_profile_enable", "ws_profile_reset", "ws_profile_kernel_count", "ws_profile_kernel_name",
            "ws_profile_read", "ws_balance_widths",
            "ws_bridge_gather", "ws_bridge_reduce_partition", "ws_bridge_fusable",
-           "ws_sp2_partial_logits", "ws_sp2_reduce_stats"]
+           "ws_sp2_partial_logits", "ws_sp2_reduce_stats", "ws_probe_mfma_loop", "ws_probe_gemm"]
 
 
 class WhaleSplitError(RuntimeError):
@@ -295,3 +300,15 @@ def sp2_reduce_stats(Z_partials, bias, labels, logsumexp, loss_rows):
     zl = (_i64 * S)(*[z.stride(0) for z in Z_partials])
     _check(lib.ws_sp2_reduce_stats(zp, zl, S, _ptr(bias), _ptr(labels), B, C, _ptr(logsumexp), _ptr(loss_rows),
                                    _stream()))
+
+
+def probe_mfma_loop(fragments, rounds, workgroups, sink):
+    """fragments: uint8/bf16 tensor of 16 * 512 * 16 bytes; sink fp32 [workgroups * 512]."""
+    _check(lib.ws_probe_mfma_loop(_ptr(fragments), int(rounds), int(workgroups), _ptr(sink), _stream()))
+
+
+def probe_gemm(A, B, C):
+    """C [N, M] bf16 <- A [M, K] . B [N, K]^T (bf16), the library's main loop alone."""
+    M, K = A.shape
+    N = B.shape[0]
+    _check(lib.ws_probe_gemm(_ptr(A), A.stride(0), _ptr(B), B.stride(0), M, N, K, _ptr(C), C.stride(0), _stream()))

@@ -7,8 +7,9 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 SRC = os.path.join(PKG, "csrc", "whalesplit.hip")
 BRIDGE_SRC = os.path.join(PKG, "csrc", "bridge.hip")
 SP2_SRC = os.path.join(PKG, "csrc", "sp2.hip")
+PROBE_SRC = os.path.join(PKG, "csrc", "probe.hip")
 HOST_SRC = os.path.join(PKG, "csrc", "balance.cpp")
-DEPS = [SRC, BRIDGE_SRC, SP2_SRC, HOST_SRC, os.path.join(PKG, "csrc", "gemm_core.h"),
+DEPS = [SRC, BRIDGE_SRC, SP2_SRC, PROBE_SRC, HOST_SRC, os.path.join(PKG, "csrc", "gemm_core.h"),
         os.path.join(os.path.dirname(PKG), "include", "whalesplit.h")]
 LIB = os.path.join(PKG, "libwhalesplit.so")
 
@@ -27,7 +28,7 @@ HOST_PASS_NOTE = "'-packed-fp32-ops' is not a recognized feature for this target
 
 
 def build(verbose=False, extra=()):
-    cmd = [HIPCC, *FLAGS, *extra, SRC, BRIDGE_SRC, SP2_SRC, HOST_SRC, "-o", LIB]
+    cmd = [HIPCC, *FLAGS, *extra, SRC, BRIDGE_SRC, SP2_SRC, PROBE_SRC, HOST_SRC, "-o", LIB]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
