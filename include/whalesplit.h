@@ -295,12 +295,14 @@ int ws_probe_gemm(const void* A, int64_t lda, const void* B, int64_t ldb, int32_
  * not thread safe).  ws_profile_enable(n) creates a pool of n event pairs (n <= 0 switches
  * timing off and frees the pool); while the pool lasts, every kernel the library launches is
  * bracketed by two events recorded on the launch stream.  ws_profile_reset() starts a new
- * measurement.  ws_profile_read() waits for the recorded events of one kernel (indices
+ * measurement.  ws_profile_pause(1) lets launches go untimed until ws_profile_pause(0) (a benchmark can
+ * time the kernels of every n-th step only, so that the event records perturb the step time less).  ws_profile_read() waits for the recorded events of one kernel (indices
  * 0 .. ws_profile_kernel_count() - 1, names from ws_profile_kernel_name) and returns the summed
  * duration in milliseconds and the number of timed launches.  total_ms and launches are HOST
  * pointers. */
 int ws_profile_enable(int32_t max_launches);
 int ws_profile_reset(void);
+int ws_profile_pause(int32_t paused);
 int32_t ws_profile_kernel_count(void);
 const char* ws_profile_kernel_name(int32_t kernel);
 int ws_profile_read(int32_t kernel, double* total_ms, int64_t* launches);

@@ -59,6 +59,8 @@ lib.ws_profile_enable.restype = ctypes.c_int
 lib.ws_profile_enable.argtypes = [_i32]
 lib.ws_profile_reset.restype = ctypes.c_int
 lib.ws_profile_reset.argtypes = []
+lib.ws_profile_pause.restype = ctypes.c_int
+lib.ws_profile_pause.argtypes = [_i32]
 lib.ws_profile_kernel_count.restype = _i32
 lib.ws_profile_kernel_count.argtypes = []
 lib.ws_profile_kernel_name.restype = ctypes.c_char_p
@@ -88,7 +90,7 @@ STATIC_SCRATCH_BYTES = 16 << 20
 
 EXPORTS = ["ws_status_string", "ws_version", "ws_fwd_workspace_bytes", "ws_split_fc_fwd", "ws_split_fc_fwd_static",
            "ws_combine_partials", "ws_bwd_workspace_bytes", "ws_split_fc_bwd", "ws_split_fc_bwd_sgd", "ws_split_fc_predict", "ws_split_fc_top1", "ws_combine_top1",
-           "ws_profile_enable", "ws_profile_reset", "ws_profile_kernel_count", "ws_profile_kernel_name",
+           "ws_profile_enable", "ws_profile_reset", "ws_profile_pause", "ws_profile_kernel_count", "ws_profile_kernel_name",
            "ws_profile_read", "ws_balance_widths",
            "ws_bridge_gather", "ws_bridge_reduce_partition", "ws_bridge_fusable",
            "ws_sp2_partial_logits", "ws_sp2_reduce_stats", "ws_probe_mfma_loop", "ws_probe_gemm"]
@@ -215,6 +217,10 @@ def profile_enable(max_launches):
 
 def profile_reset():
     _check(lib.ws_profile_reset())
+
+
+def profile_pause(paused):
+    _check(lib.ws_profile_pause(int(bool(paused))))
 
 
 def profile_read():

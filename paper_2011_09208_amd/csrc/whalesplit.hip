@@ -894,6 +894,7 @@ static const char* const kKernelNames[KID_COUNT] = {"fwd_logits_stats", "merge_c
                                                     "predict_probs", "top1_logits", "merge_top1"};
 struct ProfState {
     bool on = false;
+    bool paused = false;
     int capacity = 0, used = 0;
     hipEvent_t* start = nullptr;
     hipEvent_t* stop = nullptr;
@@ -905,7 +906,7 @@ struct ScopedTimer {
     int slot = -1;
     hipStream_t s;
     ScopedTimer(int kid, hipStream_t stream) : s(stream) {
-        if (g_prof.on && g_prof.used < g_prof.capacity) {
+        if (g_prof.on && !g_prof.paused && g_prof.used < g_prof.capacity) {
             slot = g_prof.used++;
             g_prof.kid[slot] = kid;
             (void)hipEventRecord(g_prof.start[slot], s);
@@ -1220,6 +1221,11 @@ int ws_profile_enable(int32_t max_launches) {
 
 int ws_profile_reset(void) {
     g_prof.used = 0;
+    return WS_OK;
+}
+
+int ws_profile_pause(int32_t paused) {
+    g_prof.paused = paused != 0;
     return WS_OK;
 }
 

@@ -69,6 +69,8 @@ def test_ragged_shapes_with_bias(H, B, D, widths):
 FULL_TILES_RAGGED = dict(B=300, D=64, C=256 * 70 + 5)      # 2 x 71 = 142 tiles: all full; ragged batch and class edge
 MIXED_TILES_RAGGED = dict(B=513, D=64, C=256 * 90 + 17)    # 3 x 91 = 273 tiles: 256 full + 17 x 4 thin, ragged edges
 MIXED_FIVE_BATCH_TILES = dict(B=1100, D=128, C=14000)      # 5 x 55 = 275 tiles: 256 full + 19 x 4 thin
+# the dW kernel tiles features x classes: 4 x 71 = 284 tiles, more than one round of the 256 compute units
+MIXED_DW_TILES = dict(B=300, D=1024, C=256 * 70 + 5)
 
 
 @pytest.mark.parametrize("shape,g", [
@@ -77,7 +79,9 @@ MIXED_FIVE_BATCH_TILES = dict(B=1100, D=128, C=14000)      # 5 x 55 = 275 tiles:
     (MIXED_TILES_RAGGED, 1.0 / 513),
     (MIXED_TILES_RAGGED, -2.0 / 513),
     (MIXED_FIVE_BATCH_TILES, 1.0 / 1100),
-], ids=["full-tiles", "full-tiles-negative-scale", "mixed-tiles", "mixed-tiles-negative-scale", "mixed-5-batch-tiles"])
+    (MIXED_DW_TILES, 1.0 / 300),
+], ids=["full-tiles", "full-tiles-negative-scale", "mixed-tiles", "mixed-tiles-negative-scale", "mixed-5-batch-tiles",
+        "mixed-dw-tiles"])
 def test_full_and_mixed_tile_launches_ragged_with_bias(H, shape, g):
     """The full-tile epilogues of the forward and dz kernels with everything the small shapes only reach on
     thin tiles: a batch edge inside a tile, a class edge inside a tile, a non-zero bias, a fractional and a
@@ -525,7 +529,8 @@ def _fused_sgd_parity(H, p, shards, lr, g, tag):
     (300, 256, [700, 800], 61),                 # thin tiles only
     (300, 64, [256 * 70 + 5], 62),              # 142 full tiles, ragged batch and class edge
     (513, 64, [256 * 90 + 17], 63),             # 256 full + 68 thin tiles
-], ids=["thin", "full-tiles", "mixed-tiles"])
+    (300, 1024, [256 * 70 + 5], 64),            # dW kernel: 284 tiles, more than one round
+], ids=["thin", "full-tiles", "mixed-tiles", "mixed-dw-tiles"])
 def test_backward_with_fused_sgd_update(H, B, D, widths, seed):
     C = sum(widths)
     p = inputs.make_inputs("sgd", B, D, C, w_sigma=0.3, bias_sigma=0.5, seed=seed)
