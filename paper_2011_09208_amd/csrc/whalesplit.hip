@@ -693,20 +693,43 @@ __global__ __launch_bounds__(NTHREADS) void bwd_dx(DxArgs a) {
     const Operand Bo = make_operand(a.W, a.ldw, a.C, a.D);          // classes beyond the shard read as zeros
     gemm_mainloop<KC, KS>(acc, A, Bo, bt * TILE_M, dt * TILE_N, s0 * TILE_K, ns, lds);
 
+    // The accumulator layout gives a lane four consecutive rows of one column: direct stores would be 64-byte
+    // pieces.  Instead each half of the tile (the 128 rows of one wave row) goes through LDS as fp32
+    // [128 rows][256 columns] (16-float chunks XOR-ed with (row >> 2) & 3, which spreads the four row groups of
+    // a wave's store over the banks) and leaves in whole 1 KiB rows.
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 2, wn = wave & 3, g = lane >> 4, jl = lane & 15;
     float* out = a.out + sp * a.split_stride;
+    float* tile_f32 = reinterpret_cast<float*>(lds);
+    const int d_left = a.D - dt * TILE_N;
+#pragma unroll 1
+    for (int h = 0; h < 2; ++h) {
+        if (wm == h) {
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        const int d = dt * TILE_N + wn * WAVE_N + 16 * nt + jl;
-        if (d >= a.D) continue;
+            for (int nt = 0; nt < NT; ++nt) {
+                const int col = wn * WAVE_N + 16 * nt + jl;
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
+                for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int row = bt * TILE_M + wm * WAVE_M + 16 * mt + 4 * g + v;
-                if (row < a.B) out[(int64_t)row * a.ldo + d] = acc[mt][nt][v];
+                    for (int v = 0; v < 4; ++v) {
+                        const int row = 16 * mt + 4 * g + v;
+                        tile_f32[row * 256 + ((((col >> 4) ^ ((row >> 2) & 3)) << 4) | (col & 15))] = acc[mt][nt][v];
+                    }
             }
+        }
+        __syncthreads();
+#pragma unroll 4
+        for (int i = 0; i < 16; ++i) {
+            const int q = tid + NTHREADS * i;
+            const int row = q >> 6, c4 = q & 63;
+            const int grow = bt * TILE_M + h * WAVE_M + row;
+            if (grow < a.B && 4 * c4 < d_left) {
+                const f32x4 v = *reinterpret_cast<const f32x4*>(
+                    tile_f32 + row * 256 + ((((c4 >> 2) ^ ((row >> 2) & 3)) << 4) | ((c4 & 3) << 2)));
+                *reinterpret_cast<f32x4*>(out + (int64_t)grow * a.ldo + dt * TILE_N + 4 * c4) = v;
+            }
+        }
+        __syncthreads();
     }
 }
 
