@@ -96,6 +96,60 @@ def test_two_devices_reach_the_optimum_of_the_formula_by_brute_force():
             assert balance.objective(w, C, DF) <= best + 1e-12
 
 
+def _compositions(C, N):
+    if N == 1:
+        yield (C,)
+        return
+    for a in range(C + 1):
+        for rest in _compositions(C - a, N - 1):
+            yield (a,) + rest
+
+
+def test_small_instances_against_enumeration_of_all_partitions():
+    """Independent of the algorithm's steps: for up to four devices and a few dozen columns, list EVERY integer
+    partition of the layer, keep those that satisfy the memory constraint of the formula in Section 3.3.1, and
+    check the algorithm's result against that set: it reports feasibility exactly when the set is non-empty,
+    its result lies in the set, and its value of the formula's objective is within rounding (one column per
+    device, counted on both sides of a shift) of the best value in the set.  When nothing fits, no device is
+    left over its memory while another still has room (load is conserved and only moves off over-memory
+    devices)."""
+    r = np.random.Generator(np.random.PCG64(7))
+    n_feasible = n_shifted = 0
+    for _ in range(150):
+        N = int(r.integers(2, 5))
+        C = int(r.integers(N, 25))
+        DF = r.uniform(0.5, 6.0, N).tolist()
+        TG_mem = float(r.uniform(1.0, 3.0))
+        DM = (r.uniform(0.1, 0.9, N) * TG_mem).tolist()
+        w, ok = balance.balance_widths(C, DF, DM, 2.0, TG_mem)
+        assert sum(w) == C and min(w) >= 0
+        fits = lambda part: all(part[i] / C * TG_mem <= DM[i] for i in range(N))
+        total = sum(DF)
+        value = lambda part: sum(abs(part[i] / C - DF[i] / total) for i in range(N))
+        feasible = [part for part in _compositions(C, N) if fits(part)]
+        assert ok == bool(feasible)
+        if feasible:
+            n_feasible += 1
+            assert tuple(w) in set(feasible)
+            best = min(value(part) for part in feasible)
+            assert value(w) <= best + 2.0 * N / C + 1e-12, (C, DF, DM, w, best)
+            n_shifted += w != balance.proportional_widths(C, DF)
+        else:
+            over = [i for i in range(N) if w[i] / C * TG_mem > DM[i]]
+            room = [i for i in range(N) if (w[i] + 1) / C * TG_mem <= DM[i]]
+            assert over and not room, (C, DF, DM, w)
+    assert n_feasible > 20 and n_shifted > 10        # the memory constraint was binding in many of them
+
+
+def test_ties_go_to_the_lower_device_index():
+    # two identical valleys: device 1 takes the whole excess of device 0 (it can), device 2 stays
+    w, ok = balance.balance_widths(900, [1.0, 1.0, 1.0], [0.2, 1.0, 1.0], 1.0, 1.0)
+    assert (w, ok) == ([180, 420, 300], True)
+    # two identical over-memory devices: device 0 is served first and gets the roomier valley
+    w, ok = balance.balance_widths(800, [1.0, 1.0, 1.0, 1.0], [0.125, 0.125, 0.375, 0.5], 1.0, 1.0)
+    assert ok and w[0] == 100 and w[1] == 100 and sum(w) == 800
+
+
 # ---- the library against the oracle ------------------------------------------------------------------
 
 @pytest.fixture(scope="module")
