@@ -117,6 +117,25 @@ def test_static_forward_argument_validation(ws):
     assert re.search(r"#define\s+WS_STATIC_SCRATCH_BYTES\s+\(16u\s*<<\s*20\)", text) and ws.STATIC_SCRATCH_BYTES == 16 << 20
 
 
+def test_probe_argument_validation(ws):
+    E = {ws.status_string(i): i for i in range(8)}
+
+    def gemm(A_=A, lda=64, B_=A, ldb=64, M=256, N=256, K=64, C_=A, ldc=256):
+        return ws.lib.ws_probe_gemm(A_, lda, B_, ldb, M, N, K, C_, ldc, None)
+
+    assert gemm(A_=None) == E["WS_ERR_NULL"] and gemm(C_=None) == E["WS_ERR_NULL"]
+    assert gemm(M=128) == E["WS_ERR_SHAPE"] and gemm(K=32) == E["WS_ERR_SHAPE"] and gemm(ldc=128) == E["WS_ERR_SHAPE"]
+    assert gemm(M=1 << 20, lda=4096, K=4096, ldc=1 << 20) == E["WS_ERR_SHAPE"]        # beyond 32-bit offsets
+    assert gemm(B_=A + 8) == E["WS_ERR_ALIGN"] and gemm(lda=68) == E["WS_ERR_ALIGN"]
+
+    def loop(frag=A, rounds=1, wgs=1, sink=A):
+        return ws.lib.ws_probe_mfma_loop(frag, rounds, wgs, sink, None)
+
+    assert loop(frag=None) == E["WS_ERR_NULL"] and loop(sink=None) == E["WS_ERR_NULL"]
+    assert loop(rounds=0) == E["WS_ERR_RANGE"] and loop(wgs=0) == E["WS_ERR_RANGE"] and loop(wgs=1 << 20) == E["WS_ERR_RANGE"]
+    assert loop(frag=A + 4) == E["WS_ERR_ALIGN"]
+
+
 def test_predict_argument_validation(ws):
     E = {ws.status_string(i): i for i in range(7)}
 

@@ -626,3 +626,29 @@ def test_top1_ragged_and_full_size(H):
     _top1_parity(H, q, [(0, 5), (5, 515), (520, 511)], "ragged")
     p = inputs.make_config("cfg4")
     _top1_parity(H, p, p.shards, "cfg4")
+
+
+def test_ceiling_probes_compute_what_they_time(H):
+    """The diagnostic GEMM (the library's main loop alone) against the oracle's logits, which is the same
+    product X . W^T, within bf16 rounding of the output; the MFMA-only loop leaves an exactly known checksum
+    for all-ones operands (every MFMA adds 32 to each of a wave's accumulator elements)."""
+    import torch
+    from oracle import oracle
+    from paper_2011_09208_amd import binding as ws
+    M, N, K = 512, 768, 320
+    p = inputs.make_inputs("probe", M, K, N, x_sigma=1.0, w_sigma=0.5, seed=90)      # X [M, K], W [N, K]
+    H.say(f"[parity] probe GEMM {M} x {N} x {K}")
+    A, Bm = H.dev_bf16(p.X_bits), H.dev_bf16(p.W_bits)
+    Cm = torch.full((N, M), float("nan"), device="cuda", dtype=torch.bfloat16)
+    ws.probe_gemm(A, Bm, Cm)
+    torch.cuda.synchronize()
+    ref = oracle.logits(inputs.bf16_bits_to_f64(p.X_bits), inputs.bf16_bits_to_f64(p.W_bits)).T       # [N, M]
+    got = H.bf16_to_f64(Cm)
+    assert np.all(np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-4)
+    rounds, wgs = 3, 5
+    frag = torch.ones(16 * 512 * 8, device="cuda", dtype=torch.bfloat16)
+    sink = torch.full((wgs * 512,), float("nan"), device="cuda")
+    ws.probe_mfma_loop(frag, rounds, wgs, sink)
+    torch.cuda.synchronize()
+    # per lane: 16 accumulators x 4 elements, each rounds x 8 MFMAs x 32
+    assert torch.equal(sink, torch.full_like(sink, 16 * 4 * rounds * 8 * 32.0))
