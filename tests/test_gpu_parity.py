@@ -101,6 +101,33 @@ def test_full_and_mixed_tile_launches_two_shards(H):
     _full_parity(H, p, [(0, widths[0]), (widths[0], widths[1])], g=1.0 / B, tag=f"tiles two shards B={B} widths={widths}")
 
 
+def _random_shapes(n, seed):
+    r = np.random.Generator(np.random.PCG64(seed))
+    out = []
+    for _ in range(n):
+        B = int(r.integers(1, 1400))
+        D = 64 * int(r.integers(1, 9))
+        n_shards = int(r.integers(1, 4))
+        widths = [int(w) for w in r.integers(1, 12000, size=n_shards)]
+        g = float(r.choice([1.0, 1.0 / B, -0.5, 3.0]))
+        out.append((B, D, widths, g, bool(r.integers(0, 2)), int(r.integers(0, 1 << 30))))
+    return out
+
+
+@pytest.mark.parametrize("B,D,widths,g,with_bias,seed", _random_shapes(10, 2024),
+                         ids=lambda v: str(v) if not isinstance(v, list) else "x".join(map(str, v)))
+def test_seeded_random_shapes(H, B, D, widths, g, with_bias, seed):
+    """Ten seeded random problems (row count, feature count, one to three uneven shards, gradient scale,
+    bias on or off): whatever mix of full tiles, thin tiles, ragged edges and split-K ranges they produce."""
+    C = sum(widths)
+    p = inputs.make_inputs("random", B, D, C, x_sigma=1.0, w_sigma=0.3, bias_sigma=1.0 if with_bias else None, seed=seed)
+    shards, o = [], 0
+    for w in widths:
+        shards.append((o, w))
+        o += w
+    _full_parity(H, p, shards, g=g, tag=f"random B={B} D={D} widths={widths}")
+
+
 def test_large_logits_and_dominant_class(H):
     """|z| of a few hundred: a missing max-subtraction overflows fp32; a planted dominant logit at the
     label drives loss and dz to ~0, at another class the loss equals the gap."""
