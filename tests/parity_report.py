@@ -12,8 +12,8 @@ GATES = {"lse_abs": 2e-3, "loss_rel": 1e-3, "row_max_abs": 2e-3, "sumexp_rel": 1
 def main(path):
     rows = [json.loads(l) for l in open(path) if l.strip()]
     print("Achieved GPU-vs-oracle errors of the parity suite (one MI355X), written by the tests themselves.")
-    print("Command:  WS_PARITY_LOG=gpurun_out/parity.jsonl python -m pytest tests -m gpu -x -v")
-    print("          python tests/parity_report.py gpurun_out/parity.jsonl")
+    print("Command:  WS_PARITY_LOG=parity.jsonl python -m pytest tests -m gpu -x -v")
+    print("          python tests/parity_report.py parity.jsonl")
     print("lse / row max / label logit: max absolute error; loss, sum-exp: max relative error per row;")
     print("dX, dW, db: max absolute error relative to the largest magnitude of that gradient.")
     print("Gates: " + "  ".join(f"{k} <= {v:g}" for k, v in GATES.items()))
