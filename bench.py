@@ -147,9 +147,9 @@ def main():
     torch.cuda.synchronize()
     plain_ms = (time.perf_counter() - t0) * 1e3 / args.steps
 
-    # the timed region proper: in every EVENT_EVERY-th step each kernel launch is bracketed by HIP events on its
-    # stream (a pair of records costs about as much as one of the small kernels, so not in every step)
-    EVENT_EVERY = 4
+    # the timed region proper: in about five of its steps, evenly spaced, each kernel launch is bracketed by HIP
+    # events on its stream (a pair of records costs about as much as one of the small kernels, so not in every step)
+    EVENT_EVERY = max(4, args.steps // 5)
     ws.profile_enable((args.steps // EVENT_EVERY + 1) * (7 * S + 2) + 16)
     ws.profile_reset()
     torch.cuda.synchronize()
