@@ -328,6 +328,57 @@ def test_million_class_layer_all_shards(H):
     _wide_layer_parity(H, "million", 1.0, rows_per_chunk=256)
 
 
+def test_widest_shard_the_32bit_offsets_allow(H):
+    """The kernels address an operand with 32-bit byte offsets, so a shard's weight matrix (plus 256 rows of
+    slack) must stay below 4 GiB; this runs the widest legal shard at D = 2048 — 1 048 000 classes, 4.29 GB of
+    weights, offsets up to 2^32 - 1.3e6 — through forward, combine and backward.  The oracle evaluates the layer
+    in blocks of 65 536 classes (its per-shard functions, combined by its own merge): lse and loss of every row,
+    the summed dX, db of every class and dW of the last block (the rows with the largest offsets) are compared
+    element by element."""
+    from oracle import oracle
+    B, D, C = 256, 2048, 1_048_000
+    p = inputs.make_inputs("widest", B, D, C, x_relu=True, w_sigma=0.01, seed=11)
+    H.say(f"[parity] widest shard: B={B} D={D} C_shard={C} ({C * D * 2 / 2**30:.2f} GiB of weights)")
+    g = 1.0 / B
+    got = H.run_step(p.X_bits, p.W_bits, None, p.labels, [(0, C)], g=g, keep_dW=[])
+    X = inputs.bf16_bits_to_f64(p.X_bits)
+    y = p.labels.astype(np.int64)
+    blocks = [(o, min(65_536, C - o)) for o in range(0, C, 65_536)]
+    stats = [oracle.partials(X, inputs.bf16_bits_to_f64(p.W_bits[o:o + c]), None, y, o) for o, c in blocks]
+    lse, loss = oracle.combine(*zip(*stats))
+    rep = {"lse_abs": float(np.max(np.abs(got["lse"] - lse))),
+           "loss_rel": float(np.max(np.abs(got["loss"] - loss) / np.abs(loss)))}
+    assert rep["lse_abs"] <= H.LSE_ABS and rep["loss_rel"] <= H.LOSS_REL, rep
+    dX = np.zeros((B, D))
+    db = np.empty(C)
+    for o, c in blocks:
+        gr = oracle.shard_grads(X, inputs.bf16_bits_to_f64(p.W_bits[o:o + c]), None, lse, y, o, g)
+        dX += gr["dX_partial"]
+        db[o:o + c] = gr["db"]
+    rep["dX"] = H.max_rel_to_max(got["dX"], dX)
+    rep["db"] = H.max_rel_to_max(got["db"][0], db)
+    # dW of the last block, read back from the device separately (the whole dW is 4.3 GB)
+    import torch
+    from paper_2011_09208_amd import binding as ws
+    o, c = blocks[-1]
+    Xd, Wd = H.dev_bf16(p.X_bits), H.dev_bf16(p.W_bits)
+    yd = torch.from_numpy(p.labels).cuda()
+    lsed = torch.from_numpy(lse.astype(np.float32)).cuda()
+    dXd = torch.empty((B, D), device="cuda")
+    dWd = torch.empty((C, D), device="cuda", dtype=torch.bfloat16)
+    work = torch.empty(ws.bwd_workspace_bytes(B, D, C), dtype=torch.uint8, device="cuda")
+    ws.split_fc_bwd(Xd, Wd, None, lsed, yd, 0, g, dXd, False, dWd, None, work)
+    torch.cuda.synchronize()
+    rep["dW_last_block"] = H.max_rel_to_max(H.bf16_to_f64(dWd[o:o + c]), gr["dW"])
+    rep["dW_first_block"] = H.max_rel_to_max(
+        H.bf16_to_f64(dWd[:65_536]),
+        oracle.shard_grads(X, inputs.bf16_bits_to_f64(p.W_bits[:65_536]), None, lse, y, 0, g)["dW"])
+    H.say("[parity] widest shard: " + " ".join(f"{k}={v:.2e}" for k, v in rep.items()))
+    H.record("widest shard (32-bit offset limit)", f"B={B} D={D} C={C} g={g:.3g} gate=stated", rep)
+    for k in ("dX", "db", "dW_last_block", "dW_first_block"):
+        assert rep[k] <= H.GRAD_REL_TO_MAX, (k, rep)
+
+
 def test_padded_pitches_stream_and_accumulate(H):
     """Row pitches larger than the row length for every matrix argument, a side stream, loss_mean, and
     accumulate_dx on top of a pre-filled dX: the library must honour pitches, touch nothing in the padding,
