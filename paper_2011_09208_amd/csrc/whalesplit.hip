@@ -967,7 +967,7 @@ const char* ws_status_string(int status) {
     }
 }
 
-int ws_version(void) { return 1210; }
+int ws_version(void) { return 1211; }
 
 size_t ws_fwd_workspace_bytes(int32_t B, int32_t D, int32_t C_shard) {
     return shape_ok(B, D, C_shard) ? fwd_bytes(B, C_shard) : 0;
