@@ -177,3 +177,32 @@ def compare(got, ref, labels, shards, tag="", gate="stated"):
     assert rep["dW"] <= GRAD_REL_TO_MAX, (tag, rep)
     assert rep["db"] <= GRAD_REL_TO_MAX, (tag, rep)
     return rep
+
+
+PATTERN = 0xA5
+GUARD = 8192          # bytes before and after every payload
+
+
+class Guarded:
+    """rows x cols elements of `dtype` with a row pitch of cols + pad_cols, guard bytes around them."""
+
+    def __init__(self, rows, cols, dtype, pad_cols=0, device="cuda"):
+        self.rows, self.cols, self.pitch, self.dtype = rows, cols, cols + pad_cols, dtype
+        self.es = torch.empty((), dtype=dtype).element_size()
+        self.nbytes = rows * self.pitch * self.es
+        self.raw = torch.full((GUARD + self.nbytes + GUARD,), PATTERN, dtype=torch.uint8, device=device)
+        self.t = self._payload(self.raw, dtype)
+
+    def _payload(self, raw, dtype):
+        return raw[GUARD:GUARD + self.nbytes].view(dtype).view(self.rows, self.pitch)[:, :self.cols]
+
+    def vec(self):
+        assert self.rows == 1
+        return self.t[0]
+
+    def intact_outside_payload(self):
+        r = self.raw.clone()
+        as_int = {1: torch.uint8, 2: torch.int16, 4: torch.int32}[self.es]
+        fill = {1: PATTERN, 2: int(np.int16(np.uint16(0xA5A5))), 4: int(np.int32(np.uint32(0xA5A5A5A5)))}[self.es]
+        self._payload(r, as_int).fill_(fill)
+        return bool((r == PATTERN).all())
