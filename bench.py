@@ -61,6 +61,9 @@ def main():
                     help="instead of the step, measure what the machine allows the GEMM main loop: an MFMA-only "
                          "loop and the library's main loop as a plain GEMM, on constant and on random operands, "
                          "with torch.matmul beside them as context; prints one JSON line")
+    ap.add_argument("--trace-dw", action="store_true",
+                    help="instead of timing the step, run it with the instrumented copy of the dW kernel and print "
+                         "where a workgroup's cycles go (per-tile shader-clock stamps), one JSON line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (a kernel of known traffic for scaling "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -121,6 +124,10 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+
+    if args.trace_dw:
+        print(json.dumps(trace_dw(ws, torch, np, step, args.workload, B, D, shards)), flush=True)
+        return
 
     sustained = None
     if args.sustain_seconds > 0:
@@ -343,6 +350,52 @@ def measure_extras(args, result, ws, torch, dev, X, W, y, B, D, C, work, lse, lo
             "max_abs_lse_diff_sp1_vs_one_shard": float((lse1 - lse).abs().max()),
         }
         del zparts
+
+
+def trace_dw(ws, torch, np, step, workload, B, D, shards):
+    """Where the cycles of a dW workgroup go: the step is run with the instrumented copy of the kernel (same
+    arithmetic and stores; thread 0 of every workgroup stamps the shader clock at six points and notes its compute
+    unit).  The trace kept is the one of the last shard's launch of the last step."""
+    n_dt = D // 256
+    tiles = max(n_dt * -(-c // 256) for _, c in shards)
+    trace = torch.zeros((tiles, 8), dtype=torch.int64, device="cuda:0")
+    for _ in range(20):
+        step()
+    torch.cuda.synchronize()
+    ws.profile_trace_dw(trace)
+    try:
+        for _ in range(5):
+            step()
+        torch.cuda.synchronize()
+    finally:
+        ws.profile_trace_dw(None)
+    n = n_dt * -(-shards[-1][1] // 256)
+    tr = trace[:n].cpu().numpy()
+    names = ["entry -> main loop starts", "main loop (%d k-steps)" % (-(-B // 64)), "accumulators -> LDS tile, barrier",
+             "row stores issued", "row stores acknowledged"]
+    ph = np.diff(tr[:, :6], axis=1)
+    phases = [{"phase": nm, "mean": round(float(ph[:, i].mean()), 1), "median": float(np.median(ph[:, i])),
+               "p90": float(np.percentile(ph[:, i], 90))} for i, nm in enumerate(names)]
+    total = tr[:, 5] - tr[:, 0]
+    # HW_ID: compute unit bits 8-11, shader array bit 12, shader engine bits 13-15; XCC_ID in the upper word
+    hw = tr[:, 7]
+    unit = (hw >> 32) * 4096 + ((hw >> 8) & 0xff)
+    gaps, per_unit, busy = [], [], []
+    for u in np.unique(unit):
+        rows = tr[unit == u]
+        rows = rows[np.argsort(rows[:, 0])]
+        per_unit.append(len(rows))
+        gaps.extend((rows[1:, 0] - rows[:-1, 5]).tolist())
+        busy.append(int(rows[-1, 5] - rows[0, 0]))
+    gaps = np.array(gaps if gaps else [0])
+    return {"what": "dW kernel, per-tile shader-clock stamps of thread 0 (cycles)", "workload": workload,
+            "library_version": ws.version(), "tiles": int(n), "phases": phases,
+            "tile_total": {"mean": round(float(total.mean()), 1), "median": float(np.median(total))},
+            "compute_units_seen": int(len(per_unit)),
+            "tiles_per_unit": {"min": int(min(per_unit)), "mean": round(float(np.mean(per_unit)), 2), "max": int(max(per_unit))},
+            "gap_between_tiles_on_a_unit": {"mean": round(float(gaps.mean()), 1), "median": float(np.median(gaps)),
+                                            "p90": float(np.percentile(gaps, 90))},
+            "unit_first_entry_to_last_ack": {"mean": round(float(np.mean(busy)), 1), "max": int(max(busy))}}
 
 
 def measure_ceiling(ws, torch):

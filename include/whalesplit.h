@@ -296,13 +296,24 @@ int ws_probe_gemm(const void* A, int64_t lda, const void* B, int64_t ldb, int32_
  * timing off and frees the pool); while the pool lasts, every kernel the library launches is
  * bracketed by two events recorded on the launch stream.  ws_profile_reset() starts a new
  * measurement.  ws_profile_pause(1) lets launches go untimed until ws_profile_pause(0) (a benchmark can
- * time the kernels of every n-th step only, so that the event records perturb the step time less).  ws_profile_read() waits for the recorded events of one kernel (indices
+ * time the kernels of every n-th step only, so that the event records perturb the step time less).
+ * ws_profile_read() waits for the recorded events of one kernel (indices
  * 0 .. ws_profile_kernel_count() - 1, names from ws_profile_kernel_name) and returns the summed
  * duration in milliseconds and the number of timed launches.  total_ms and launches are HOST
- * pointers. */
+ * pointers.
+ *
+ * ws_profile_trace_dw(trace, tiles): while `trace` (DEVICE, 8-byte aligned, uint64 [tiles][8], owned by the
+ * caller, who keeps it alive until tracing is switched off and the last traced call has finished) is set,
+ * the dW kernel of every backward call runs as an instrumented copy with the same arithmetic and stores;
+ * for its output tile t (class tile t / (D / 256), feature tile t % (D / 256)) thread 0 of the workgroup
+ * writes trace[t][0..5] = shader clock at: kernel entry, start of the main loop, end of the main loop, output
+ * tile staged in LDS, row stores issued, row stores acknowledged; [6] = workgroup id; [7] = XCC_ID << 32 |
+ * HW_ID (which compute unit).  A backward call with more than `tiles` output tiles returns WS_ERR_WORKSPACE
+ * before launching anything.  trace = NULL switches tracing off. */
 int ws_profile_enable(int32_t max_launches);
 int ws_profile_reset(void);
 int ws_profile_pause(int32_t paused);
+int ws_profile_trace_dw(void* trace, int64_t tiles);
 int32_t ws_profile_kernel_count(void);
 const char* ws_profile_kernel_name(int32_t kernel);
 int ws_profile_read(int32_t kernel, double* total_ms, int64_t* launches);

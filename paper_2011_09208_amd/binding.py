@@ -61,6 +61,8 @@ lib.ws_profile_reset.restype = ctypes.c_int
 lib.ws_profile_reset.argtypes = []
 lib.ws_profile_pause.restype = ctypes.c_int
 lib.ws_profile_pause.argtypes = [_i32]
+lib.ws_profile_trace_dw.restype = ctypes.c_int
+lib.ws_profile_trace_dw.argtypes = [ctypes.c_void_p, _i64]
 lib.ws_profile_kernel_count.restype = _i32
 lib.ws_profile_kernel_count.argtypes = []
 lib.ws_profile_kernel_name.restype = ctypes.c_char_p
@@ -90,7 +92,7 @@ STATIC_SCRATCH_BYTES = 16 << 20
 
 EXPORTS = ["ws_status_string", "ws_version", "ws_fwd_workspace_bytes", "ws_split_fc_fwd", "ws_split_fc_fwd_static",
            "ws_combine_partials", "ws_bwd_workspace_bytes", "ws_split_fc_bwd", "ws_split_fc_bwd_sgd", "ws_split_fc_predict", "ws_split_fc_top1", "ws_combine_top1",
-           "ws_profile_enable", "ws_profile_reset", "ws_profile_pause", "ws_profile_kernel_count", "ws_profile_kernel_name",
+           "ws_profile_enable", "ws_profile_reset", "ws_profile_pause", "ws_profile_trace_dw", "ws_profile_kernel_count", "ws_profile_kernel_name",
            "ws_profile_read", "ws_balance_widths",
            "ws_bridge_gather", "ws_bridge_reduce_partition", "ws_bridge_fusable",
            "ws_sp2_partial_logits", "ws_sp2_reduce_stats", "ws_probe_mfma_loop", "ws_probe_gemm"]
@@ -221,6 +223,16 @@ def profile_reset():
 
 def profile_pause(paused):
     _check(lib.ws_profile_pause(int(bool(paused))))
+
+
+def profile_trace_dw(trace):
+    """trace: int64 CUDA tensor [tiles, 8] that the dW kernel of the following backward calls fills with
+    per-tile clock stamps (see the header), or None to switch tracing off."""
+    if trace is None:
+        _check(lib.ws_profile_trace_dw(None, 0))
+    else:
+        assert trace.dtype == torch.int64 and trace.is_contiguous() and trace.shape[1] == 8
+        _check(lib.ws_profile_trace_dw(_ptr(trace), trace.shape[0]))
 
 
 def profile_read():

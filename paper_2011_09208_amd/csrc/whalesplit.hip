@@ -788,12 +788,12 @@ struct DwArgs {
 
 // dW^T tile: M = features d (A = X^T, k contiguous), N = classes (B operand = dz read k-strided, the
 // narrower side of a wave's sub-tile as in bwd_dx), K = batch rows.
-__global__ __launch_bounds__(NTHREADS) void bwd_dw(DwArgs a, FinishArgs fin) {
-    __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
-    if ((int)blockIdx.x >= fin.first_block) {
-        finish_bwd(fin, (int)blockIdx.x - fin.first_block);
-        return;
-    }
+// TRACE: thread 0 of the workgroup also writes the shader clock at six points of its tile, and which compute
+// unit it ran on, to trace[8 * tile ..] (diagnostics; the arithmetic and the stores are the same).
+template <bool TRACE>
+__device__ __forceinline__ void dw_tile(const DwArgs& a, char* lds, unsigned long long* trace) {
+    unsigned long long stamp[6];
+    if (TRACE) stamp[0] = __builtin_readcyclecounter();
     const int tile = xcd_logical_tile(a.nDT * a.nCT);
     if (tile < 0) return;
     const int dt = tile % a.nDT, ct = tile / a.nDT;    // feature tiles fastest: neighbours share the dz panel
@@ -802,16 +802,52 @@ __global__ __launch_bounds__(NTHREADS) void bwd_dw(DwArgs a, FinishArgs fin) {
     zero_acc(acc);
     const Operand A = make_operand(a.XT, a.ldxt, a.D, a.ldxt);
     const Operand Bo = make_operand(a.dZ, a.ldz, a.Bpad, a.ldz);
+    if (TRACE) stamp[1] = __builtin_readcyclecounter();
     gemm_mainloop<KC, KS>(acc, A, Bo, dt * TILE_M, ct * TILE_N, 0, a.k_steps, lds);
+    if (TRACE) stamp[2] = __builtin_readcyclecounter();
 
     // [class][feature] tile through LDS, then whole 512-byte rows of dW
     acc_to_lds_bf16(acc, lds);
     __syncthreads();
+    if (TRACE) stamp[3] = __builtin_readcyclecounter();
     const int c_left = a.C - ct * TILE_N, d_left = a.D - dt * TILE_M;
     uint16_t* out = a.dW + (int64_t)ct * TILE_N * a.lddw + dt * TILE_M;
     const int n_valid = c_left < TILE_N ? c_left : TILE_N, m_valid = d_left < TILE_M ? d_left : TILE_M;
     if (a.sgd) lds_tile_update_rows(lds, out, a.lddw, n_valid, m_valid, a.lr);
     else lds_tile_store_rows(lds, out, a.lddw, n_valid, m_valid);
+    if (TRACE) {
+        stamp[4] = __builtin_readcyclecounter();
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");           // this wave's stores have been acknowledged
+        stamp[5] = __builtin_readcyclecounter();
+        if (threadIdx.x == 0) {
+            // hardware registers HW_ID (4: wave, SIMD, compute unit, shader array and engine) and XCC_ID (20)
+            const unsigned long long hw = __builtin_amdgcn_s_getreg((31 << 11) | 4);
+            const unsigned long long xcc = __builtin_amdgcn_s_getreg((3 << 11) | 20);
+            unsigned long long* t = trace + 8 * (int64_t)tile;
+#pragma unroll
+            for (int i = 0; i < 6; ++i) t[i] = stamp[i];
+            t[6] = (unsigned long long)blockIdx.x;
+            t[7] = (xcc << 32) | hw;
+        }
+    }
+}
+
+__global__ __launch_bounds__(NTHREADS) void bwd_dw(DwArgs a, FinishArgs fin) {
+    __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
+    if ((int)blockIdx.x >= fin.first_block) {
+        finish_bwd(fin, (int)blockIdx.x - fin.first_block);
+        return;
+    }
+    dw_tile<false>(a, lds, nullptr);
+}
+
+__global__ __launch_bounds__(NTHREADS) void bwd_dw_traced(DwArgs a, FinishArgs fin, unsigned long long* trace) {
+    __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
+    if ((int)blockIdx.x >= fin.first_block) {
+        finish_bwd(fin, (int)blockIdx.x - fin.first_block);
+        return;
+    }
+    dw_tile<true>(a, lds, trace);
 }
 
 // ---- host side -----------------------------------------------------------------------------------
@@ -924,6 +960,10 @@ struct ProfState {
     int* kid = nullptr;
 };
 static ProfState g_prof;
+
+// ws_profile_trace_dw: where the dW kernel of the following backward calls writes its per-tile clock stamps.
+static unsigned long long* g_dw_trace = nullptr;
+static int64_t g_dw_trace_tiles = 0;
 
 struct ScopedTimer {
     int slot = -1;
@@ -1076,6 +1116,7 @@ static int run_bwd(const void* X, int64_t ldx, const void* W_shard, int64_t ldw,
         return WS_ERR_SHAPE;
     if (!workspace || workspace_bytes < p.dz_bytes + p.xt_bytes + p.dbp_bytes + p.parts_bytes) return WS_ERR_WORKSPACE;
     if (!aligned(workspace, 16)) return WS_ERR_ALIGN;
+    if (g_dw_trace != nullptr && (int64_t)p.nDT * p.nCT > g_dw_trace_tiles) return WS_ERR_WORKSPACE;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     uint16_t* dZ = static_cast<uint16_t*>(workspace);
@@ -1121,7 +1162,11 @@ static int run_bwd(const void* X, int64_t ldx, const void* W_shard, int64_t ldw,
     f.sgd = sgd; f.lr = lr;
     f.first_block = xcd_grid(p.nDT * p.nCT);
     f.n_blocks = (f.parts || f.db_part) ? SIDE_BLOCKS : 0;
-    WS_LAUNCH(KID_DW, bwd_dw, dim3(f.first_block + f.n_blocks), dim3(NTHREADS), s, w, f);
+    if (g_dw_trace != nullptr) {
+        WS_LAUNCH(KID_DW, bwd_dw_traced, dim3(f.first_block + f.n_blocks), dim3(NTHREADS), s, w, f, g_dw_trace);
+    } else {
+        WS_LAUNCH(KID_DW, bwd_dw, dim3(f.first_block + f.n_blocks), dim3(NTHREADS), s, w, f);
+    }
     return launch_status();
 }
 
@@ -1249,6 +1294,19 @@ int ws_profile_reset(void) {
 
 int ws_profile_pause(int32_t paused) {
     g_prof.paused = paused != 0;
+    return WS_OK;
+}
+
+int ws_profile_trace_dw(void* device_trace, int64_t tiles) {
+    if (device_trace == nullptr) {
+        g_dw_trace = nullptr;
+        g_dw_trace_tiles = 0;
+        return WS_OK;
+    }
+    if (tiles <= 0) return WS_ERR_SHAPE;
+    if (!aligned(device_trace, 8)) return WS_ERR_ALIGN;
+    g_dw_trace = static_cast<unsigned long long*>(device_trace);
+    g_dw_trace_tiles = tiles;
     return WS_OK;
 }
 

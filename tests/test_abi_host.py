@@ -206,3 +206,16 @@ def test_top1_argument_validation(ws):
     assert ws.lib.ws_combine_top1(A, A, 0, 4, 4, A, A, None) == E["WS_ERR_RANGE"]
     assert ws.lib.ws_combine_top1(A, A, 2, 4, 3, A, A, None) == E["WS_ERR_SHAPE"]
     assert ws.lib.ws_combine_top1(A, None, 2, 4, 4, A, A, None) == E["WS_ERR_NULL"]
+
+
+def test_dw_trace_argument_validation(ws):
+    E = {ws.status_string(i): i for i in range(8)}
+    trace = ws.lib.ws_profile_trace_dw
+    try:
+        assert trace(A, 0) == E["WS_ERR_SHAPE"] and trace(A + 4, 16) == E["WS_ERR_ALIGN"]
+        assert trace(A, 5) == E["WS_OK"]
+        # 2 feature tiles x 3 class tiles = 6 output tiles do not fit 5 trace rows: refused before any launch
+        assert _bwd(ws, D=512, ldx=512, ldw=512, lddx=512, lddw=512, C=600) == E["WS_ERR_WORKSPACE"]
+        assert _bwd(ws, X=None) == E["WS_ERR_NULL"]                   # the ordinary checks still come first
+    finally:
+        assert trace(None, 0) == E["WS_OK"]

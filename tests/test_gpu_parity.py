@@ -730,3 +730,52 @@ def test_ceiling_probes_compute_what_they_time(H):
     torch.cuda.synchronize()
     # per lane: 16 accumulators x 4 elements, each rounds x 8 MFMAs x 32
     assert torch.equal(sink, torch.full_like(sink, 16 * 4 * rounds * 8 * 32.0))
+
+
+def test_traced_dw_kernel_writes_the_same_gradients(H):
+    """The instrumented copy of the dW kernel (per-tile clock stamps for the benchmark's trace) must leave
+    every output bit for bit as the plain kernel does, stamp every tile once with clocks that never run
+    backwards, and refuse a trace buffer that is too small before launching anything."""
+    import torch
+    from paper_2011_09208_amd import binding as ws
+    B, D, C = 300, 512, 17925            # 2 feature tiles x 71 class tiles, ragged in rows and classes
+    p = inputs.make_inputs("trace", B, D, C, x_sigma=1.0, w_sigma=0.2, bias_sigma=0.5, seed=17)
+    H.say(f"[parity] traced dW kernel: B={B} D={D} C={C}")
+    X, W = H.dev_bf16(p.X_bits), H.dev_bf16(p.W_bits)
+    bias = torch.from_numpy(p.bias).cuda()
+    y = torch.from_numpy(np.ascontiguousarray(p.labels, dtype=np.int32)).cuda()
+    work = torch.empty(max(ws.fwd_workspace_bytes(B, D, C), ws.bwd_workspace_bytes(B, D, C)), dtype=torch.uint8,
+                       device="cuda")
+    m, s, t, lse, loss = (torch.empty(B, device="cuda") for _ in range(5))
+    ws.split_fc_fwd(X, W, bias, y, 0, m, s, t, work)
+    ws.combine_partials(m.view(1, B), s.view(1, B), t.view(1, B), lse, loss, None)
+
+    def bwd():
+        dX = torch.full((B, D), float("nan"), device="cuda")
+        dW = torch.full((C, D), float("nan"), device="cuda", dtype=torch.bfloat16)
+        db = torch.full((C,), float("nan"), device="cuda")
+        ws.split_fc_bwd(X, W, bias, lse, y, 0, 1.0 / B, dX, False, dW, db, work)
+        torch.cuda.synchronize()
+        return dX, dW, db
+
+    plain = bwd()
+    tiles = (D // 256) * (-(-C // 256))
+    trace = torch.zeros((tiles, 8), dtype=torch.int64, device="cuda")
+    try:
+        ws.profile_trace_dw(trace[:tiles - 1].contiguous())
+        with pytest.raises(ws.WhaleSplitError) as err:
+            bwd()
+        assert err.value.status == 5                      # WS_ERR_WORKSPACE
+        ws.profile_trace_dw(trace)
+        traced = bwd()
+    finally:
+        ws.profile_trace_dw(None)
+    again = bwd()
+    for a, b, c in zip(plain, traced, again):
+        assert torch.equal(a.view(torch.int16) if a.dtype == torch.bfloat16 else a.view(torch.int32),
+                           b.view(torch.int16) if b.dtype == torch.bfloat16 else b.view(torch.int32))
+        assert torch.equal(b.view(torch.int16) if b.dtype == torch.bfloat16 else b.view(torch.int32),
+                           c.view(torch.int16) if c.dtype == torch.bfloat16 else c.view(torch.int32))
+    tr = trace.cpu().numpy()
+    assert np.all(tr[:, 0] > 0) and np.all(np.diff(tr[:, :6], axis=1) >= 0)
+    assert len(np.unique(tr[:, 6])) == tiles              # one workgroup per tile
