@@ -2,6 +2,8 @@
 workspace-taking entry point's, bit for bit (same kernels), and against the fp64 oracle to the stated gate,
 on two calls in a row, the second with a smaller input (the built-in scratch keeps the first call's
 contents)."""
+import gc
+
 import numpy as np
 import pytest
 
@@ -23,11 +25,16 @@ def _one_call(H, ws, torch, B, D, C, off, seed):
     work = torch.empty(ws.fwd_workspace_bytes(B, D, C), dtype=torch.uint8, device=dev)
     ws.split_fc_fwd(X, W, bias, y, off, *ref_out, work)
     got = [torch.full((B,), float("nan"), device=dev) for _ in range(3)]
+    # nothing may be allocated by the call: neither through torch (count of its allocator's allocations; tensors of
+    # earlier tests may be freed at any time, so not the bytes in use) nor behind its back (the device's free memory)
+    gc.collect()
     torch.cuda.synchronize()
-    before = torch.cuda.memory_allocated()
+    n_alloc = torch.cuda.memory_stats()["allocation.all.allocated"]
+    free_before = torch.cuda.mem_get_info()[0]
     ws.split_fc_fwd_static(X, W, bias, y, off, *got)
     torch.cuda.synchronize()
-    assert torch.cuda.memory_allocated() == before
+    assert torch.cuda.memory_stats()["allocation.all.allocated"] == n_alloc
+    assert torch.cuda.mem_get_info()[0] >= free_before
     for g, r in zip(got, ref_out):
         assert torch.equal(g.view(torch.int32), r.view(torch.int32))
     m, s, t = oracle.partials(inputs.bf16_bits_to_f64(p.X_bits), inputs.bf16_bits_to_f64(p.W_bits),
