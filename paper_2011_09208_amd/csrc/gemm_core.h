@@ -197,9 +197,13 @@ struct SlotSched {
 // an operand's extent read as zeros.
 typedef f32x4 acc_t[MT][NT];
 
+// `descending` (uniform over the workgroup): walk the k-steps from the last to the first.  Tiles that follow each
+// other on a compute unit and share an operand panel can alternate the direction, so that the second finds
+// the end of the panel, which the first has just read, still in the L2.
 template <int AKIND, int BKIND>
 __device__ __forceinline__ void gemm_mainloop(acc_t& acc, const Operand& A, const Operand& Bop,
-                                              int m0, int n0, int k_begin, int k_steps, char* lds) {
+                                              int m0, int n0, int k_begin, int k_steps, char* lds,
+                                              bool descending = false) {
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
@@ -234,7 +238,9 @@ __device__ __forceinline__ void gemm_mainloop(acc_t& acc, const Operand& A, cons
                 acc[HM * half + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[aset][i], bfr[bset][j],
                                                                                 acc[HM * half + i][j], 0, 0, 0);
     };
-    auto kofs = [&](int step) { return k_begin + (step < last ? step : last) * TILE_K; };
+    const int k_first = descending ? k_begin + last * TILE_K : k_begin;
+    const int k_stride = descending ? -TILE_K : TILE_K;
+    auto kofs = [&](int step) { return k_first + (step < last ? step : last) * k_stride; };
     const uint32_t a_off = tile_lane_offset<AKIND>(A, m0, tid);
     const uint32_t b_off = tile_lane_offset<BKIND>(Bop, n0, tid);
     auto g2r = [&](int quarter, int step) {
@@ -340,7 +346,7 @@ typedef f32x4 thin_acc_t[THIN_MT][THIN_NT];
 // barrier slot B multiplies substep 1 while the first fragments of the next k-step are read.
 // k-steps beyond the last are clamped to the last one (a harmless reload).  Ends with a workgroup barrier.
 __device__ __forceinline__ void thin_mainloop(thin_acc_t& acc, const Operand& A, const Operand& Bop, int m0, int n0,
-                                              int k_begin, int k_steps, char* lds) {
+                                              int k_begin, int k_steps, char* lds, bool descending = false) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     FragAddr<KC, THIN_MT> fa;
     FragAddr<KC, THIN_NT> fb;
@@ -349,11 +355,13 @@ __device__ __forceinline__ void thin_mainloop(thin_acc_t& acc, const Operand& A,
     const uint32_t a_off = tile_lane_offset<KC>(A, m0, tid);
     const uint32_t b_off = tile_lane_offset<KC>(Bop, n0, tid);       // thread t: row t / 8 of the 64, chunk t % 8
     const int last = k_steps - 1;
+    const int k_first = descending ? k_begin + last * TILE_K : k_begin;
+    const int k_stride = descending ? -TILE_K : TILE_K;
     constexpr int NM = THIN_MT * THIN_NT, NR = THIN_MT + THIN_NT;
     u32x4 ra[4], rb;
     bf16x8 af[2][THIN_MT], bfr[2][THIN_NT];
     auto g2r = [&](int step) {
-        const int k0 = k_begin + (step < last ? step : last) * TILE_K;
+        const int k0 = k_first + (step < last ? step : last) * k_stride;
 #pragma unroll
         for (int q = 0; q < 4; ++q) ra[q] = quarter_g2r<KC>(A, a_off, k0, q);
         rb = quarter_g2r<KC>(Bop, b_off, k0, 0);

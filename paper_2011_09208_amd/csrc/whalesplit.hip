@@ -103,6 +103,16 @@ __device__ __forceinline__ TileRef logits_tile_ref(const FcArgs& a) {
     return r;
 }
 
+// Direction in which the logits of class tile ct walk the features.  An XCD works through a contiguous range
+// of tiles, 32 at a time, so a compute unit's next tile lies about 32 tile ids further on; alternating the
+// direction between such groups lets it find the end of the X panels, which it has just read, still in the
+// L2 (launches of one round have nothing to gain and keep one direction).  A function of the class tile and
+// the launch shape alone, so that every kernel (and the thin and the full version of a tile) adds the
+// products of a logit in the same order.
+__device__ __forceinline__ bool logits_descending(const FcArgs& a, int ct) {
+    return a.nBT * a.nCT > 256 && (((ct * a.nBT) >> 5) & 1) != 0;
+}
+
 // Runs the logits GEMM of one 256-class x 256-row tile and leaves z (bias added, padding = -inf)
 // in acc.  M = classes (A = W_s, KC), N = batch rows (B operand = X, KC), K = D.
 __device__ __forceinline__ void logits_tile(acc_t& acc, const FcArgs& a, int ct, int bt, char* lds,
@@ -110,7 +120,7 @@ __device__ __forceinline__ void logits_tile(acc_t& acc, const FcArgs& a, int ct,
     zero_acc(acc);
     const Operand A = make_operand(a.W, a.ldw, a.C, a.D);
     const Operand Bo = make_operand(a.X, a.ldx, a.B, a.D);
-    gemm_mainloop<KC, KC>(acc, A, Bo, ct * TILE_M, bt * TILE_N, 0, a.D / TILE_K, lds);
+    gemm_mainloop<KC, KC>(acc, A, Bo, ct * TILE_M, bt * TILE_N, 0, a.D / TILE_K, lds, logits_descending(a, ct));
     const int tid = threadIdx.x;
     const bool has_bias = a.bias != nullptr;
     if (has_bias) {
@@ -136,7 +146,7 @@ __device__ __forceinline__ void logits_thin(thin_acc_t& acc, const FcArgs& a, in
         for (int j = 0; j < THIN_NT; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
     const Operand A = make_operand(a.W, a.ldw, a.C, a.D);
     const Operand Bo = make_operand(a.X, a.ldx, a.B, a.D);
-    thin_mainloop(acc, A, Bo, ct * TILE_M, bt * TILE_N + piece * THIN_N, 0, a.D / TILE_K, lds);
+    thin_mainloop(acc, A, Bo, ct * TILE_M, bt * TILE_N + piece * THIN_N, 0, a.D / TILE_K, lds, logits_descending(a, ct));
     const int tid = threadIdx.x, wave = tid >> 6, g = (tid & 63) >> 4;
     if (a.bias != nullptr) {
         if (tid < TILE_M) {
@@ -803,7 +813,9 @@ __device__ __forceinline__ void dw_tile(const DwArgs& a, char* lds, unsigned lon
     const Operand A = make_operand(a.XT, a.ldxt, a.D, a.ldxt);
     const Operand Bo = make_operand(a.dZ, a.ldz, a.Bpad, a.ldz);
     if (TRACE) stamp[1] = __builtin_readcyclecounter();
-    gemm_mainloop<KC, KS>(acc, A, Bo, dt * TILE_M, ct * TILE_N, 0, a.k_steps, lds);
+    // workgroups are dealt out 256 at a time, 32 to each XCD: alternate the direction round by round, so that a
+    // compute unit's next tile finds the end of the X^T panels, which it has just read, still in the L2
+    gemm_mainloop<KC, KS>(acc, A, Bo, dt * TILE_M, ct * TILE_N, 0, a.k_steps, lds, ((blockIdx.x >> 8) & 1) != 0);
     if (TRACE) stamp[2] = __builtin_readcyclecounter();
 
     // [class][feature] tile through LDS, then whole 512-byte rows of dW
@@ -1007,7 +1019,7 @@ const char* ws_status_string(int status) {
     }
 }
 
-int ws_version(void) { return 1211; }
+int ws_version(void) { return 1212; }
 
 size_t ws_fwd_workspace_bytes(int32_t B, int32_t D, int32_t C_shard) {
     return shape_ok(B, D, C_shard) ? fwd_bytes(B, C_shard) : 0;
