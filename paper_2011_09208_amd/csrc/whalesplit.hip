@@ -78,6 +78,7 @@ struct FcArgs {
     int Bpad;        // B rounded up to 256
     int nBT, nCT;    // tiles along the batch and class dimensions
     TilePlan plan;   // which of the nBT * nCT tiles run as full tiles and which as four thin tiles each
+    int last_tile_first;   // walk the full tiles from the last to the first
 };
 
 // The tile a workgroup of a logits kernel works on: full (piece < 0) or thin piece 0 .. 3 of it.
@@ -96,6 +97,7 @@ __device__ __forceinline__ TileRef logits_tile_ref(const FcArgs& a) {
         r.piece = q & 3;
     } else {
         tile = xcd_logical_tile(a.plan.n_full);
+        if (a.last_tile_first && tile >= 0) tile = a.plan.n_full - 1 - tile;
     }
     r.valid = tile >= 0;
     r.ct = tile / a.nBT;       // batch tiles fastest: neighbours share the W panel
@@ -1019,7 +1021,7 @@ const char* ws_status_string(int status) {
     }
 }
 
-int ws_version(void) { return 1212; }
+int ws_version(void) { return 1213; }
 
 size_t ws_fwd_workspace_bytes(int32_t B, int32_t D, int32_t C_shard) {
     return shape_ok(B, D, C_shard) ? fwd_bytes(B, C_shard) : 0;
@@ -1047,6 +1049,7 @@ static int launch_fwd(const void* X, int64_t ldx, const void* W_shard, int64_t l
                       const int32_t* labels, int32_t B, int32_t D, int32_t C_shard, int32_t class_offset,
                       float* row_max, float* row_sumexp, float* label_logit, void* workspace, void* stream) {
     FcArgs a;
+    a.last_tile_first = 0;
     a.X = static_cast<const uint16_t*>(X); a.ldx = ldx;
     a.W = static_cast<const uint16_t*>(W_shard); a.ldw = ldw;
     a.bias = b_shard; a.labels = labels;
@@ -1137,6 +1140,7 @@ static int run_bwd(const void* X, int64_t ldx, const void* W_shard, int64_t ldw,
     float* parts = db_part + (size_t)4 * p.nBT * p.Cpad;
 
     FcArgs a;
+    a.last_tile_first = 1;   // the forward call has just read the last class tiles of W: they may still be in the Infinity Cache
     a.X = static_cast<const uint16_t*>(X); a.ldx = ldx;
     a.W = static_cast<const uint16_t*>(W_shard); a.ldw = ldw;
     a.bias = b_shard; a.labels = labels;
@@ -1211,6 +1215,7 @@ int ws_split_fc_predict(const void* X, int64_t ldx, const void* W_shard, int64_t
     if (!aligned(X, 16) || !aligned(W_shard, 16) || !aligned(P, 16) || ldx % 8 || ldw % 8 || ldp % 8) return WS_ERR_ALIGN;
     if (!aligned(logsumexp, 4) || (b_shard && !aligned(b_shard, 4))) return WS_ERR_ALIGN;
     FcArgs a;
+    a.last_tile_first = 0;
     a.X = static_cast<const uint16_t*>(X); a.ldx = ldx;
     a.W = static_cast<const uint16_t*>(W_shard); a.ldw = ldw;
     a.bias = b_shard; a.labels = nullptr;
@@ -1238,6 +1243,7 @@ int ws_split_fc_top1(const void* X, int64_t ldx, const void* W_shard, int64_t ld
     if (!workspace || workspace_bytes < fwd_bytes(B, C_shard)) return WS_ERR_WORKSPACE;
     if (!aligned(workspace, 16)) return WS_ERR_ALIGN;
     FcArgs a;
+    a.last_tile_first = 0;
     a.X = static_cast<const uint16_t*>(X); a.ldx = ldx;
     a.W = static_cast<const uint16_t*>(W_shard); a.ldw = ldw;
     a.bias = b_shard; a.labels = nullptr;
