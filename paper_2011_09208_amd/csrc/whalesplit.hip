@@ -87,6 +87,31 @@ struct TileRef {
     bool valid;
 };
 
+// Tile t of a logits launch -> (class tile, batch tile).  Up to four batch tiles: batch tiles fastest, so the 32
+// consecutive tiles that an XCD runs at a time share a W panel four ways and cover 32 / nBT class tiles.  More
+// batch tiles: blocks of 8 class tiles x 4 batch tiles (12 operand panels for 32 tiles instead of 33), the
+// batch blocks of one block of class tiles one after the other, so that consecutive rounds share its W panels.
+__device__ __forceinline__ void logits_tile_coords(const FcArgs& a, int t, int& ct, int& bt) {
+    if (a.nBT <= 4) {
+        ct = t / a.nBT;
+        bt = t % a.nBT;
+        return;
+    }
+    const int per_block = 8 * a.nBT;
+    const int cb = t / per_block, r = t - cb * per_block;
+    const int rest = a.nCT - 8 * cb, h = rest < 8 ? rest : 8;     // class tiles in this block
+    const int full_bb = a.nBT >> 2, in_full = h * 4 * full_bb;
+    if (r < in_full) {
+        const int bb = r / (h * 4), q = r - bb * (h * 4);
+        ct = 8 * cb + (q >> 2);
+        bt = 4 * bb + (q & 3);
+    } else {
+        const int w = a.nBT & 3, q = r - in_full;
+        ct = 8 * cb + q / w;
+        bt = 4 * full_bb + q % w;
+    }
+}
+
 __device__ __forceinline__ TileRef logits_tile_ref(const FcArgs& a) {
     TileRef r;
     r.piece = -1;
@@ -100,19 +125,21 @@ __device__ __forceinline__ TileRef logits_tile_ref(const FcArgs& a) {
         if (a.last_tile_first && tile >= 0) tile = a.plan.n_full - 1 - tile;
     }
     r.valid = tile >= 0;
-    r.ct = tile / a.nBT;       // batch tiles fastest: neighbours share the W panel
-    r.bt = tile % a.nBT;
+    r.ct = r.bt = 0;
+    if (r.valid) logits_tile_coords(a, tile, r.ct, r.bt);
     return r;
 }
 
-// Direction in which the logits of class tile ct walk the features.  An XCD works through a contiguous range
-// of tiles, 32 at a time, so a compute unit's next tile lies about 32 tile ids further on; alternating the
-// direction between such groups lets it find the end of the X panels, which it has just read, still in the
-// L2 (launches of one round have nothing to gain and keep one direction).  A function of the class tile and
-// the launch shape alone, so that every kernel (and the thin and the full version of a tile) adds the
-// products of a logit in the same order.
-__device__ __forceinline__ bool logits_descending(const FcArgs& a, int ct) {
-    return a.nBT * a.nCT > 256 && (((ct * a.nBT) >> 5) & 1) != 0;
+// Direction in which the logits of tile (ct, bt) walk the features.  A compute unit's next tile lies about 32
+// tile ids further on, in the next group of class tiles (up to four batch tiles) or the next batch block of the
+// same class tiles (more); alternating the direction between such groups lets it find the end of the panels
+// that the two tiles share, which it has just read, still in the L2 (launches of one round have nothing to gain
+// and keep one direction).  A function of the tile's coordinates and the launch shape alone, so that every
+// kernel (and the thin and the full version of a tile) adds the products of a logit in the same order.
+__device__ __forceinline__ bool logits_descending(const FcArgs& a, int ct, int bt) {
+    if (a.nBT * a.nCT <= 256) return false;
+    if (a.nBT <= 4) return (((ct * a.nBT) >> 5) & 1) != 0;
+    return (((ct >> 3) ^ (bt >> 2)) & 1) != 0;
 }
 
 // Runs the logits GEMM of one 256-class x 256-row tile and leaves z (bias added, padding = -inf)
@@ -122,7 +149,7 @@ __device__ __forceinline__ void logits_tile(acc_t& acc, const FcArgs& a, int ct,
     zero_acc(acc);
     const Operand A = make_operand(a.W, a.ldw, a.C, a.D);
     const Operand Bo = make_operand(a.X, a.ldx, a.B, a.D);
-    gemm_mainloop<KC, KC>(acc, A, Bo, ct * TILE_M, bt * TILE_N, 0, a.D / TILE_K, lds, logits_descending(a, ct));
+    gemm_mainloop<KC, KC>(acc, A, Bo, ct * TILE_M, bt * TILE_N, 0, a.D / TILE_K, lds, logits_descending(a, ct, bt));
     const int tid = threadIdx.x;
     const bool has_bias = a.bias != nullptr;
     if (has_bias) {
@@ -148,7 +175,7 @@ __device__ __forceinline__ void logits_thin(thin_acc_t& acc, const FcArgs& a, in
         for (int j = 0; j < THIN_NT; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
     const Operand A = make_operand(a.W, a.ldw, a.C, a.D);
     const Operand Bo = make_operand(a.X, a.ldx, a.B, a.D);
-    thin_mainloop(acc, A, Bo, ct * TILE_M, bt * TILE_N + piece * THIN_N, 0, a.D / TILE_K, lds, logits_descending(a, ct));
+    thin_mainloop(acc, A, Bo, ct * TILE_M, bt * TILE_N + piece * THIN_N, 0, a.D / TILE_K, lds, logits_descending(a, ct, bt));
     const int tid = threadIdx.x, wave = tid >> 6, g = (tid & 63) >> 4;
     if (a.bias != nullptr) {
         if (tid < TILE_M) {
@@ -692,9 +719,12 @@ __global__ __launch_bounds__(NTHREADS) void bwd_dx(DxArgs a) {
     __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
     const int tile = xcd_logical_tile(a.nDT * a.nBT * a.splits);
     if (tile < 0) return;
-    const int bt = tile % a.nBT;
-    const int dt = (tile / a.nBT) % a.nDT;
-    const int sp = tile / (a.nBT * a.nDT);
+    // The 32 consecutive tiles that an XCD runs at a time should share their panels: up to four batch tiles, batch
+    // tiles fastest (all tiles of 32 / nBT feature tiles); more, feature tiles fastest (the tiles that share a dz
+    // panel, the larger operand, sit on one XCD).
+    const int td = tile % (a.nBT * a.nDT), sp = tile / (a.nBT * a.nDT);
+    const int bt = a.nBT <= 4 ? td % a.nBT : td / a.nDT;
+    const int dt = a.nBT <= 4 ? td / a.nBT : td % a.nDT;
     const int s0 = sp * a.steps_per_split;
     int ns = a.steps_total - s0;
     ns = ns < a.steps_per_split ? ns : a.steps_per_split;
@@ -1021,7 +1051,7 @@ const char* ws_status_string(int status) {
     }
 }
 
-int ws_version(void) { return 1213; }
+int ws_version(void) { return 1214; }
 
 size_t ws_fwd_workspace_bytes(int32_t B, int32_t D, int32_t C_shard) {
     return shape_ok(B, D, C_shard) ? fwd_bytes(B, C_shard) : 0;
