@@ -371,6 +371,7 @@ def trace_dw(ws, torch, np, step, workload, B, D, shards):
         ws.profile_trace_dw(None)
     n = n_dt * -(-shards[-1][1] // 256)
     tr = trace[:n].cpu().numpy()
+    tr = tr[tr[:, 0] > 0]            # tiles of a last round that ran as thin tiles are not traced
     names = ["entry -> main loop starts", "main loop (%d k-steps)" % (-(-B // 64)), "accumulators -> LDS tile, barrier",
              "row stores issued", "row stores acknowledged"]
     ph = np.diff(tr[:, :6], axis=1)
@@ -389,7 +390,7 @@ def trace_dw(ws, torch, np, step, workload, B, D, shards):
         busy.append(int(rows[-1, 5] - rows[0, 0]))
     gaps = np.array(gaps if gaps else [0])
     return {"what": "dW kernel, per-tile shader-clock stamps of thread 0 (cycles)", "workload": workload,
-            "library_version": ws.version(), "tiles": int(n), "phases": phases,
+            "library_version": ws.version(), "tiles": int(n), "tiles_traced": int(len(tr)), "phases": phases,
             "tile_total": {"mean": round(float(total.mean()), 1), "median": float(np.median(total))},
             "compute_units_seen": int(len(per_unit)),
             "tiles_per_unit": {"min": int(min(per_unit)), "mean": round(float(np.mean(per_unit)), 2), "max": int(max(per_unit))},

@@ -339,43 +339,88 @@ constexpr int THIN_MT = THIN_WAVE_M / 16, THIN_NT = THIN_N / 16;
 constexpr int THIN_STAGE_BYTES = OPERAND_TILE_BYTES + THIN_N * TILE_K * 2;    // 32 KiB A + 8 KiB B
 typedef f32x4 thin_acc_t[THIN_MT][THIN_NT];
 
+// A thin tile's B operand may also be k-strided (memory [k][col]): LDS then holds [64 k][64 cols], 128 bytes per
+// k-row, 16-byte chunks XOR-ed with thin_ks_swizzle(k).  A transposing read is served half a wave at a time:
+// 8 k-rows (k & 3 and bit 3 of k), two adjacent chunks and both halves of a chunk; k & 1 picks the 128-byte
+// half of the bank window, bits 1 and 3 of k go to chunk bits 1-2, the adjacent chunks differ in bit 0.
+__device__ __forceinline__ int thin_ks_swizzle(int k) { return (((k >> 1) & 1) << 1) | (((k >> 3) & 1) << 2); }
+
+// Byte offset of a thread's chunk of the k-strided thin B tile whose first column is n0, at k = 0: thread t
+// moves chunk t % 8 of k-row t / 8.
+__device__ __forceinline__ uint32_t thin_ks_lane_offset(const Operand& op, int n0, int tid) {
+    return ((uint32_t)(tid >> 3) * op.ld + (uint32_t)(n0 + (tid & 7) * 8)) * 2u;
+}
+__device__ __forceinline__ u32x4 thin_ks_g2r(const Operand& op, uint32_t lane_off, int k0) {
+    return __builtin_amdgcn_raw_buffer_load_b128(op.rsrc, (int)lane_off, (int)((uint32_t)k0 * op.ld * 2u), 0);
+}
+__device__ __forceinline__ void thin_ks_r2s(char* lds, const u32x4& v, int tid) {
+    const int kr = tid >> 3, ch = tid & 7;
+    *reinterpret_cast<u32x4*>(lds + kr * 128 + ((ch ^ thin_ks_swizzle(kr)) << 4)) = v;
+}
+struct ThinKsFrag {
+    int off[THIN_N / 16];
+    __device__ __forceinline__ void init(int lane) {
+        const int i = lane & 15, g = lane >> 4;
+        const int krow = 8 * g + (i >> 2);
+#pragma unroll
+        for (int t = 0; t < THIN_N / 16; ++t) {
+            const int col = 16 * t + 4 * (i & 3);
+            off[t] = krow * 128 + (((col >> 3) ^ thin_ks_swizzle(krow)) << 4) + ((col & 7) << 1);
+        }
+    }
+    __device__ __forceinline__ bf16x8 load(const char* lds, int t, int s) const {
+        typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
+        const char* p = lds + off[t] + s * (32 * 128);
+        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p));
+        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 4 * 128));
+        s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        return __builtin_bit_cast(bf16x8, v);
+    }
+};
+
 // acc[mt][nt] += A(m0 .. m0+255, k) * B(n0 .. n0+63, k) for k in [k_begin, k_begin + 64 * k_steps);
-// wave w holds rows 32 w .. 32 w + 31.  Two LDS stages, the same software pipeline as the full tile in
+// wave w holds rows 32 w .. 32 w + 31.  BKIND KS: B is k-strided, n0 its first column.  Two LDS stages, the same software pipeline as the full tile in
 // two slots of 8 MFMAs per k-step: slot A multiplies k-substep 0 while the fragments of substep 1 are
 // read, the next k-step goes registers -> LDS and the one after it global -> registers; after the
 // barrier slot B multiplies substep 1 while the first fragments of the next k-step are read.
 // k-steps beyond the last are clamped to the last one (a harmless reload).  Ends with a workgroup barrier.
+template <int BKIND = KC>
 __device__ __forceinline__ void thin_mainloop(thin_acc_t& acc, const Operand& A, const Operand& Bop, int m0, int n0,
                                               int k_begin, int k_steps, char* lds, bool descending = false) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     FragAddr<KC, THIN_MT> fa;
     FragAddr<KC, THIN_NT> fb;
+    ThinKsFrag fbs;
     fa.init(lane, wave * THIN_WAVE_M);
-    fb.init(lane, 0);
+    if (BKIND == KC) fb.init(lane, 0);
+    else fbs.init(lane);
     const uint32_t a_off = tile_lane_offset<KC>(A, m0, tid);
-    const uint32_t b_off = tile_lane_offset<KC>(Bop, n0, tid);       // thread t: row t / 8 of the 64, chunk t % 8
+    // KC: thread t moves chunk t % 8 of row t / 8 of the 64; KS: chunk t % 8 of k-row t / 8
+    const uint32_t b_off = BKIND == KC ? tile_lane_offset<KC>(Bop, n0, tid) : thin_ks_lane_offset(Bop, n0, tid);
     const int last = k_steps - 1;
     const int k_first = descending ? k_begin + last * TILE_K : k_begin;
     const int k_stride = descending ? -TILE_K : TILE_K;
-    constexpr int NM = THIN_MT * THIN_NT, NR = THIN_MT + THIN_NT;
+    constexpr int NM = THIN_MT * THIN_NT, NR = THIN_MT + THIN_NT * (BKIND == KC ? 1 : 2);
     u32x4 ra[4], rb;
     bf16x8 af[2][THIN_MT], bfr[2][THIN_NT];
     auto g2r = [&](int step) {
         const int k0 = k_first + (step < last ? step : last) * k_stride;
 #pragma unroll
         for (int q = 0; q < 4; ++q) ra[q] = quarter_g2r<KC>(A, a_off, k0, q);
-        rb = quarter_g2r<KC>(Bop, b_off, k0, 0);
+        rb = BKIND == KC ? quarter_g2r<KC>(Bop, b_off, k0, 0) : thin_ks_g2r(Bop, b_off, k0);
     };
     auto r2s = [&](char* stage) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) quarter_r2s<KC>(stage, ra[q], tid, q);
-        quarter_r2s<KC>(stage + OPERAND_TILE_BYTES, rb, tid, 0);
+        if (BKIND == KC) quarter_r2s<KC>(stage + OPERAND_TILE_BYTES, rb, tid, 0);
+        else thin_ks_r2s(stage + OPERAND_TILE_BYTES, rb, tid);
     };
     auto frags = [&](int set, const char* stage, int s) {
 #pragma unroll
         for (int i = 0; i < THIN_MT; ++i) af[set][i] = fa.load(stage, i, s);
 #pragma unroll
-        for (int i = 0; i < THIN_NT; ++i) bfr[set][i] = fb.load(stage + OPERAND_TILE_BYTES, i, s);
+        for (int i = 0; i < THIN_NT; ++i)
+            bfr[set][i] = BKIND == KC ? fb.load(stage + OPERAND_TILE_BYTES, i, s) : fbs.load(stage + OPERAND_TILE_BYTES, i, s);
     };
     auto mfmas = [&](int set) {
 #pragma unroll

@@ -826,6 +826,7 @@ struct DwArgs {
     int nDT, nCT, k_steps;
     uint16_t* dW; int64_t lddw;          // sgd: the weights themselves, updated in place
     int sgd; float lr;
+    TilePlan plan;                       // full tiles, and the thin ones a ragged last round is cut into
 };
 
 // dW^T tile: M = features d (A = X^T, k contiguous), N = classes (B operand = dz read k-strided, the
@@ -836,7 +837,7 @@ template <bool TRACE>
 __device__ __forceinline__ void dw_tile(const DwArgs& a, char* lds, unsigned long long* trace) {
     unsigned long long stamp[6];
     if (TRACE) stamp[0] = __builtin_readcyclecounter();
-    const int tile = xcd_logical_tile(a.nDT * a.nCT);
+    const int tile = xcd_logical_tile(a.plan.n_full);
     if (tile < 0) return;
     const int dt = tile % a.nDT, ct = tile / a.nDT;    // feature tiles fastest: neighbours share the dz panel
 
@@ -876,10 +877,50 @@ __device__ __forceinline__ void dw_tile(const DwArgs& a, char* lds, unsigned lon
     }
 }
 
+// Thin tile of dW: all 256 features of feature tile dt x 64 classes (piece 0 .. 3 of class tile ct); the dz
+// operand is k-strided.  Used for the tiles of a ragged last round when the contraction is long (the host
+// decides, plan_tiles); not traced.
+__device__ __forceinline__ void dw_thin(const DwArgs& a, int q, char* lds) {
+    const int tile = a.plan.n_full + (q >> 2), piece = q & 3;
+    const int dt = tile % a.nDT, ct = tile / a.nDT;
+    const int c0 = ct * TILE_N + piece * THIN_N;
+    if (c0 >= a.C) return;                              // a piece entirely beyond the shard's classes
+    thin_acc_t acc;
+#pragma unroll
+    for (int i = 0; i < THIN_MT; ++i)
+#pragma unroll
+        for (int j = 0; j < THIN_NT; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const Operand A = make_operand(a.XT, a.ldxt, a.D, a.ldxt);
+    const Operand Bo = make_operand(a.dZ, a.ldz, a.Bpad, a.ldz);
+    thin_mainloop<KS>(acc, A, Bo, dt * TILE_M, c0, 0, a.k_steps, lds);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 4, jl = lane & 15;
+#pragma unroll
+    for (int nt = 0; nt < THIN_NT; ++nt) {
+        const int n = 16 * nt + jl;
+#pragma unroll
+        for (int mt = 0; mt < THIN_MT; ++mt) {
+            u32x2 pk;
+            pk[0] = pack_bf16(acc[mt][nt][0], acc[mt][nt][1]);
+            pk[1] = pack_bf16(acc[mt][nt][2], acc[mt][nt][3]);
+            *reinterpret_cast<u32x2*>(lds + out_tile_offset(n, wave * THIN_WAVE_M + 16 * mt + 4 * g)) = pk;
+        }
+    }
+    __syncthreads();
+    const int c_left = a.C - c0, d_left = a.D - dt * TILE_M;
+    uint16_t* out = a.dW + (int64_t)c0 * a.lddw + dt * TILE_M;
+    const int n_valid = c_left < THIN_N ? c_left : THIN_N, m_valid = d_left < TILE_M ? d_left : TILE_M;
+    if (a.sgd) lds_tile_update_rows(lds, out, a.lddw, n_valid, m_valid, a.lr);
+    else lds_tile_store_rows(lds, out, a.lddw, n_valid, m_valid);
+}
+
 __global__ __launch_bounds__(NTHREADS) void bwd_dw(DwArgs a, FinishArgs fin) {
     __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
     if ((int)blockIdx.x >= fin.first_block) {
         finish_bwd(fin, (int)blockIdx.x - fin.first_block);
+        return;
+    }
+    if ((int)blockIdx.x >= a.plan.thin_first) {
+        dw_thin(a, (int)blockIdx.x - a.plan.thin_first, lds);
         return;
     }
     dw_tile<false>(a, lds, nullptr);
@@ -889,6 +930,10 @@ __global__ __launch_bounds__(NTHREADS) void bwd_dw_traced(DwArgs a, FinishArgs f
     __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
     if ((int)blockIdx.x >= fin.first_block) {
         finish_bwd(fin, (int)blockIdx.x - fin.first_block);
+        return;
+    }
+    if ((int)blockIdx.x >= a.plan.thin_first) {
+        dw_thin(a, (int)blockIdx.x - a.plan.thin_first, lds);
         return;
     }
     dw_tile<true>(a, lds, trace);
@@ -911,6 +956,9 @@ static TilePlan plan_tiles(int n_tiles, bool allow_thin) {
     t.thin_first = xcd_grid(t.n_full);
     return t;
 }
+// Shortest contraction (k-steps of 64 batch rows) for which the dW kernel cuts the tiles of a ragged last round
+// into thin ones: measured slower at 16 k-steps (the last round is mostly output there), faster at 128.
+static const int DW_THIN_MIN_K_STEPS = 48;
 // Workgroups appended to a GEMM launch for its small side job (X^T, the final reductions).
 static const int SIDE_BLOCKS = 128;
 
@@ -1051,7 +1099,7 @@ const char* ws_status_string(int status) {
     }
 }
 
-int ws_version(void) { return 1214; }
+int ws_version(void) { return 1215; }
 
 size_t ws_fwd_workspace_bytes(int32_t B, int32_t D, int32_t C_shard) {
     return shape_ok(B, D, C_shard) ? fwd_bytes(B, C_shard) : 0;
@@ -1200,13 +1248,15 @@ static int run_bwd(const void* X, int64_t ldx, const void* W_shard, int64_t ldw,
     w.nDT = p.nDT; w.nCT = p.nCT; w.k_steps = (B + TILE_K - 1) / TILE_K;
     w.dW = static_cast<uint16_t*>(dW_shard); w.lddw = lddw;
     w.sgd = sgd; w.lr = lr;
+    // thin tiles pay off only where a tile is long: with few k-steps the last round is mostly output
+    w.plan = plan_tiles(p.nDT * p.nCT, w.k_steps >= DW_THIN_MIN_K_STEPS);
     FinishArgs f;
     f.parts = direct ? nullptr : parts; f.splits = p.splits; f.split_stride = (int64_t)B * D;
     f.B = B; f.D = D; f.dX = dX_partial; f.lddx = lddx; f.accumulate = accumulate_dx;
     f.db_part = db_shard ? db_part : nullptr; f.n_db_parts = 4 * p.nBT; f.db_stride = p.Cpad;
     f.C = C_shard; f.db = db_shard;
     f.sgd = sgd; f.lr = lr;
-    f.first_block = xcd_grid(p.nDT * p.nCT);
+    f.first_block = w.plan.thin_first + w.plan.n_thin;
     f.n_blocks = (f.parts || f.db_part) ? SIDE_BLOCKS : 0;
     if (g_dw_trace != nullptr) {
         WS_LAUNCH(KID_DW, bwd_dw_traced, dim3(f.first_block + f.n_blocks), dim3(NTHREADS), s, w, f, g_dw_trace);

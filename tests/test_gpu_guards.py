@@ -39,6 +39,7 @@ SHAPES = [
     ("full and thin tiles", 513, 64, 23057),
     ("five batch tiles", 1100, 128, 14000),
     ("dW in full and thin tiles", 300, 1024, 17925),
+    ("dW in thin tiles, long contraction", 3100, 320, 600),
 ]
 
 

@@ -71,6 +71,10 @@ MIXED_TILES_RAGGED = dict(B=513, D=64, C=256 * 90 + 17)    # 3 x 91 = 273 tiles:
 MIXED_FIVE_BATCH_TILES = dict(B=1100, D=128, C=14000)      # 5 x 55 = 275 tiles: 256 full + 19 x 4 thin
 # the dW kernel tiles features x classes: 4 x 71 = 284 tiles, more than one round of the 256 compute units
 MIXED_DW_TILES = dict(B=300, D=1024, C=256 * 70 + 5)
+# long contractions in the dW kernel (B >= 3072 rows: 48 k-steps), where it cuts a ragged last round into thin
+# tiles too; 13 batch tiles (logits tiles numbered in blocks of 8 class x 4 batch tiles, the last block 1 wide)
+LONG_K_DW_ALL_THIN = dict(B=3100, D=320, C=600)              # dW: 2 x 3 = 6 tiles, all thin; ragged feature tile
+LONG_K_DW_MIXED = dict(B=3100, D=2304, C=256 * 29 - 7)       # dW: 9 x 29 = 261 tiles: 256 full + 5 x 4 thin
 
 
 @pytest.mark.parametrize("shape,g", [
@@ -80,8 +84,10 @@ MIXED_DW_TILES = dict(B=300, D=1024, C=256 * 70 + 5)
     (MIXED_TILES_RAGGED, -2.0 / 513),
     (MIXED_FIVE_BATCH_TILES, 1.0 / 1100),
     (MIXED_DW_TILES, 1.0 / 300),
+    (LONG_K_DW_ALL_THIN, 1.0 / 3100),
+    (LONG_K_DW_MIXED, -3.0 / 3100),
 ], ids=["full-tiles", "full-tiles-negative-scale", "mixed-tiles", "mixed-tiles-negative-scale", "mixed-5-batch-tiles",
-        "mixed-dw-tiles"])
+        "mixed-dw-tiles", "long-k-dw-thin-tiles", "long-k-dw-mixed-tiles-negative-scale"])
 def test_full_and_mixed_tile_launches_ragged_with_bias(H, shape, g):
     """The full-tile epilogues of the forward and dz kernels with everything the small shapes only reach on
     thin tiles: a batch edge inside a tile, a class edge inside a tile, a non-zero bias, a fractional and a
@@ -608,7 +614,8 @@ def _fused_sgd_parity(H, p, shards, lr, g, tag):
     (300, 64, [256 * 70 + 5], 62),              # 142 full tiles, ragged batch and class edge
     (513, 64, [256 * 90 + 17], 63),             # 256 full + 68 thin tiles
     (300, 1024, [256 * 70 + 5], 64),            # dW kernel: 284 tiles, more than one round
-], ids=["thin", "full-tiles", "mixed-tiles", "mixed-dw-tiles"])
+    (3100, 320, [600], 65),                     # dW kernel: long contraction, thin tiles
+], ids=["thin", "full-tiles", "mixed-tiles", "mixed-dw-tiles", "long-k-dw-thin"])
 def test_backward_with_fused_sgd_update(H, B, D, widths, seed):
     C = sum(widths)
     p = inputs.make_inputs("sgd", B, D, C, w_sigma=0.3, bias_sigma=0.5, seed=seed)
