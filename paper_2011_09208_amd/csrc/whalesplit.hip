@@ -14,7 +14,11 @@
 //   bwd_dw             dW_s = dz^T . X; its surplus workgroups sum the split-K partials of dX
 //                      (optionally accumulating into the caller's dX) and the db partials
 // fwd_logits_stats and bwd_recompute_dz run the tiles of a ragged last round (256 compute units) as
-// four thin 256 x 64 tiles each (logits_thin, fwd_stats_thin, dz_thin; plan_tiles on the host).
+// four thin 256 x 64 tiles each (logits_thin, fwd_stats_thin, dz_thin; plan_tiles on the host); bwd_dw
+// does the same where the contraction is long (dw_thin).
+// Tile orders and cache reuse: each XCD walks a contiguous range of tiles whose neighbours share operand
+// panels (logits_tile_coords, bwd_dx, dw_tile); every other round of tiles walks the contraction backwards
+// (logits_descending, dw_tile) and bwd_recompute_dz starts with the tiles that fwd_logits_stats ended on.
 #include <hip/hip_runtime.h>
 #include <algorithm>
 #include <atomic>
